@@ -1,0 +1,2 @@
+"""Plain CPU oracle of the denoising path (test infrastructure, not product code)."""
+from . import dit, sampler  # noqa: F401

@@ -1,0 +1,119 @@
+"""CPU oracle: noise schedule, guidance, the deterministic DDIM update, and the
+cache-hit resume loop.
+
+TEST INFRASTRUCTURE ONLY (see oracle/dit.py): never imported by the product path.
+
+What it follows.  The paper runs a 50-step sampler of the DDIM family (Sec. 2.1;
+Sec. 5 "Implementation") whose steps are strictly sequential, each step's output
+being the next step's input.  On a cache hit the stored latent of step k is set
+as the input and generation proceeds from the next step (Sec. 2.2; Sec. 3.2
+"Cache lookup"; Sec. 4.2.2: a cache of the 10th step lets the request proceed
+from the 11th).  So `denoise_resume(x_k, k)` runs steps k+1 .. N of the very same
+step function a cache miss runs from k = 0.
+
+Readings the paper leaves open, as taken here:
+  * beta is linear in i between beta_start and beta_end over `train_steps`
+    training timesteps; abar_t = prod_{i<=t} (1 - beta_i), evaluated in float64.
+  * the N sampling timesteps are tau_j = j * (train_steps / N), j = 0..N-1, visited
+    in descending order; step s (1-based) goes from t = tau_{N-s} to tau_{N-s-1},
+    and the last step goes to abar_prev = 1 (it returns the x0 estimate).
+  * eta = 0: no noise is drawn, the update is a deterministic function of
+    (x_t, eps).
+  * classifier-free guidance: eps = eps_u + s (eps_c - eps_u), eps_u from a given
+    'null' text embedding.
+
+Pins (tests/test_oracle_sampler.py): closed-form schedule values, monotonicity,
+exact recovery x_prev = sqrt(abar_prev) x0 + sqrt(1-abar_prev) eps* when the
+network returns the true eps*, eps = 0 scaling, guidance special cases (s = 0,
+s = 1, cond == null), resume composition, resume(N) = identity, and the number
+of network evaluations of resume(k).
+"""
+from __future__ import annotations
+
+import math
+from typing import Callable, Optional
+
+import numpy as np
+
+from . import dit
+
+
+def alphas_cumprod(train_steps=1000, beta_start=1e-4, beta_end=2e-2):
+    """abar_t for t = 0..train_steps-1, float64."""
+    i = np.arange(train_steps, dtype=np.float64)
+    beta = beta_start + (beta_end - beta_start) * i / (train_steps - 1)
+    return np.cumprod(1.0 - beta)
+
+
+def sampling_timesteps(num_steps, train_steps=1000):
+    """tau_0..tau_{N-1} ascending: tau_j = j * (train_steps // N)."""
+    return np.arange(num_steps, dtype=np.int64) * (train_steps // num_steps)
+
+
+def step_coefficients(sched, step):
+    """(t, abar_t, abar_prev) of the step-th (1-based) of sched.num_steps steps."""
+    N = sched.num_steps
+    if not 1 <= step <= N:
+        raise ValueError("step out of range")
+    tau = sampling_timesteps(N, sched.train_steps)
+    abar = alphas_cumprod(sched.train_steps, sched.beta_start, sched.beta_end)
+    t = int(tau[N - step])
+    abar_prev = 1.0 if step == N else float(abar[tau[N - step - 1]])
+    return t, float(abar[t]), abar_prev
+
+
+def guide(eps_cond, eps_null, scale):
+    """Classifier-free guidance: eps_u + s (eps_c - eps_u)."""
+    return eps_null + scale * (eps_cond - eps_null)
+
+
+def ddim_update(x_t, eps, abar_t, abar_prev):
+    """Deterministic DDIM (eta = 0), eps-prediction:
+    x0 = (x_t - sqrt(1-abar_t) eps) / sqrt(abar_t);
+    x_prev = sqrt(abar_prev) x0 + sqrt(1-abar_prev) eps."""
+    x0 = (x_t - math.sqrt(1.0 - abar_t) * eps) / math.sqrt(abar_t)
+    return math.sqrt(abar_prev) * x0 + math.sqrt(1.0 - abar_prev) * eps
+
+
+def denoise_step(cfg, weights, latent, cond, null_cond, sched, step, dtype=np.float64,
+                 eps_fn: Optional[Callable] = None, return_eps=False):
+    """One denoising step for R requests.
+
+    latent [R,T,H,W,C]; cond [R,L,dt]; null_cond [L,dt] or None (no guidance).
+    eps_fn(latent_r, text, t) replaces the network (used by the pins).
+    Returns the latents after the step, same shape, in `dtype`."""
+    if sched.eta != 0.0:
+        raise ValueError("only the deterministic sampler (eta = 0) is defined here")
+    t, abar_t, abar_prev = step_coefficients(sched, step)
+    if eps_fn is None:
+        W = {k: np.asarray(v, dtype=dtype) for k, v in weights.items()}
+        eps_fn = lambda x, txt, tt: dit.forward(cfg, W, x, txt, tt, dtype=None)
+    lat = np.asarray(latent, dtype=dtype)
+    out = np.empty_like(lat)
+    eps_out = np.empty_like(lat)
+    for r in range(lat.shape[0]):
+        eps = eps_fn(lat[r], np.asarray(cond[r], dtype=dtype), t)
+        if null_cond is not None:
+            eps_u = eps_fn(lat[r], np.asarray(null_cond, dtype=dtype), t)
+            eps = guide(eps, eps_u, sched.guidance_scale)
+        eps_out[r] = eps
+        out[r] = ddim_update(lat[r], eps, abar_t, abar_prev)
+    return (out, eps_out) if return_eps else out
+
+
+def denoise_resume(cfg, weights, latent, cond, null_cond, sched, k, dtype=np.float64,
+                   eps_fn: Optional[Callable] = None, on_step: Optional[Callable] = None):
+    """Run steps k+1 .. N from the stored step-k latent (k = 0: a full run from
+    noise; k = N: nothing to do).  on_step(step, latent) is called after each step."""
+    N = sched.num_steps
+    if not 0 <= k <= N:
+        raise ValueError("k out of range")
+    x = np.asarray(latent, dtype=dtype)
+    if eps_fn is None and k < N:
+        W = {kk: np.asarray(v, dtype=dtype) for kk, v in weights.items()}
+        eps_fn = lambda xx, txt, tt: dit.forward(cfg, W, xx, txt, tt, dtype=None)
+    for s in range(k + 1, N + 1):
+        x = denoise_step(cfg, None, x, cond, null_cond, sched, s, dtype=dtype, eps_fn=eps_fn)
+        if on_step is not None:
+            on_step(s, x)
+    return x

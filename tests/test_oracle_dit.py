@@ -1,0 +1,450 @@
+"""Pins of the network oracle (oracle/dit.py) against things that are not itself:
+brute-force loops, closed forms, invariants and an independently written
+evaluation of the whole tiny network."""
+import math
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from oracle import dit
+from paper_2501_04012_amd import synth
+
+RNG = np.random.default_rng(7)
+
+
+# --------------------------------------------------------------------------- attention core
+
+def brute_attention(q, k, v):
+    """O(Nq*Nk*d) python loops in float64, no max subtraction, no matmul."""
+    nq, d = q.shape
+    nk = k.shape[0]
+    out = np.zeros((nq, v.shape[1]))
+    for i in range(nq):
+        w = [math.exp(sum(float(q[i, c]) * float(k[j, c]) for c in range(d)) / math.sqrt(d))
+             for j in range(nk)]
+        z = sum(w)
+        for j in range(nk):
+            for c in range(v.shape[1]):
+                out[i, c] += w[j] / z * float(v[j, c])
+    return out
+
+
+@pytest.mark.parametrize("nq,nk,d", [(1, 1, 1), (5, 7, 3), (16, 16, 8), (3, 12, 4)])
+def test_attention_matches_brute_force(nq, nk, d):
+    q, k, v = RNG.standard_normal((nq, d)), RNG.standard_normal((nk, d)), RNG.standard_normal((nk, d))
+    np.testing.assert_allclose(dit.attention(q, k, v), brute_attention(q, k, v), rtol=1e-12, atol=1e-13)
+
+
+def test_attention_sharp_rows_match_brute_force():
+    q, k, v = synth.sharp_qkv(3, 6, 9, 4, gain=3.0)
+    np.testing.assert_allclose(dit.attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64)),
+                               brute_attention(q, k, v), rtol=1e-10, atol=1e-12)
+
+
+def test_softmax_rows_sum_to_one_and_survive_large_logits():
+    s = RNG.standard_normal((13, 29)) * 50 + 700.0     # exp(700+) overflows without the max shift
+    p = dit.softmax_rows(s)
+    assert np.all(np.isfinite(p))
+    np.testing.assert_allclose(p.sum(-1), 1.0, atol=1e-12)
+    p32 = dit.softmax_rows(s.astype(np.float32))
+    np.testing.assert_allclose(p32.sum(-1), 1.0, atol=1e-6)
+
+
+def test_attention_equal_keys_gives_mean_of_values():
+    q = RNG.standard_normal((4, 6))
+    k = np.tile(RNG.standard_normal((1, 6)), (9, 1))
+    v = RNG.standard_normal((9, 6))
+    np.testing.assert_allclose(dit.attention(q, k, v), np.tile(v.mean(0), (4, 1)), atol=1e-13)
+
+
+def test_attention_single_key_returns_its_value():
+    q, k, v = RNG.standard_normal((5, 4)), RNG.standard_normal((1, 4)), RNG.standard_normal((1, 4))
+    np.testing.assert_allclose(dit.attention(q, k, v), np.tile(v, (5, 1)), atol=1e-14)
+
+
+def test_attention_scale_is_inverse_sqrt_d():
+    # two keys, d = 4: weights must be softmax((q.k1, q.k2)/2)
+    q = np.array([[1.0, 2.0, 0.0, -1.0]])
+    k = np.array([[0.5, 0.5, 1.0, 0.0], [1.0, -1.0, 0.0, 2.0]])
+    v = np.array([[1.0, 0, 0, 0], [0, 1.0, 0, 0]])
+    l1, l2 = (0.5 + 1.0) / 2, (1 - 2 - 2) / 2
+    w1 = math.exp(l1) / (math.exp(l1) + math.exp(l2))
+    np.testing.assert_allclose(dit.attention(q, k, v)[0, :2], [w1, 1 - w1], atol=1e-14)
+
+
+def _attn_weights(D, rng):
+    return (rng.standard_normal((D, 3 * D)) * 0.3, rng.standard_normal(3 * D) * 0.1,
+            rng.standard_normal((D, D)) * 0.3, rng.standard_normal(D) * 0.1)
+
+
+def test_self_attention_token_permutation_equivariance():
+    rng = np.random.default_rng(11)
+    u = rng.standard_normal((10, 12))
+    w = _attn_weights(12, rng)
+    perm = rng.permutation(10)
+    a = dit.self_attention(u, *w, heads=3)
+    b = dit.self_attention(u[perm], *w, heads=3)
+    np.testing.assert_allclose(b, a[perm], atol=1e-12)
+
+
+def test_attention_key_permutation_invariance():
+    q, k, v = RNG.standard_normal((4, 5)), RNG.standard_normal((8, 5)), RNG.standard_normal((8, 5))
+    perm = RNG.permutation(8)
+    np.testing.assert_allclose(dit.attention(q, k[perm], v[perm]), dit.attention(q, k, v), atol=1e-13)
+
+
+def test_self_attention_heads_are_column_groups():
+    """A per-head brute-force evaluation with explicit column slices."""
+    rng = np.random.default_rng(12)
+    n, D, h = 6, 8, 2
+    d = D // h
+    u = rng.standard_normal((n, D))
+    wqkv, bqkv, wp, bp = _attn_weights(D, rng)
+    qkv = np.einsum("nd,de->ne", u, wqkv) + bqkv
+    cat = np.zeros((n, D))
+    for i in range(h):
+        q = qkv[:, i * d:(i + 1) * d]
+        k = qkv[:, D + i * d:D + (i + 1) * d]
+        v = qkv[:, 2 * D + i * d:2 * D + (i + 1) * d]
+        cat[:, i * d:(i + 1) * d] = brute_attention(q, k, v)
+    want = np.einsum("nd,de->ne", cat, wp) + bp
+    np.testing.assert_allclose(dit.self_attention(u, wqkv, bqkv, wp, bp, h), want, atol=1e-12)
+
+
+def test_self_attention_groups_do_not_mix_and_q_rows_subset():
+    rng = np.random.default_rng(13)
+    u = rng.standard_normal((3, 5, 8))
+    w = _attn_weights(8, rng)
+    full = dit.self_attention(u, *w, heads=2)
+    for g in range(3):
+        np.testing.assert_allclose(full[g], dit.self_attention(u[g], *w, heads=2), atol=1e-13)
+    rows = np.array([4, 1])
+    np.testing.assert_allclose(dit.self_attention(u[0], *w, heads=2, q_rows=rows), full[0][rows], atol=1e-13)
+
+
+def test_cross_attention_matches_brute_force():
+    rng = np.random.default_rng(14)
+    n, L, D, h = 5, 3, 8, 2
+    d = D // h
+    u, y = rng.standard_normal((n, D)), rng.standard_normal((L, D))
+    wq, bq = rng.standard_normal((D, D)) * 0.3, rng.standard_normal(D) * 0.1
+    wkv, bkv = rng.standard_normal((D, 2 * D)) * 0.3, rng.standard_normal(2 * D) * 0.1
+    wp, bp = rng.standard_normal((D, D)) * 0.3, rng.standard_normal(D) * 0.1
+    q = u @ wq + bq
+    kv = y @ wkv + bkv
+    cat = np.zeros((n, D))
+    for i in range(h):
+        cat[:, i * d:(i + 1) * d] = brute_attention(q[:, i * d:(i + 1) * d], kv[:, i * d:(i + 1) * d],
+                                                    kv[:, D + i * d:D + (i + 1) * d])
+    np.testing.assert_allclose(dit.cross_attention(u, y, wq, bq, wkv, bkv, wp, bp, h), cat @ wp + bp, atol=1e-12)
+
+
+# --------------------------------------------------------------------------- pointwise pieces
+
+def test_layernorm_moments_and_invariances():
+    x = RNG.standard_normal((7, 64)) * 3 + 5
+    eps = 1e-6
+    y = dit.layernorm(x, eps)
+    np.testing.assert_allclose(y.mean(-1), 0, atol=1e-12)
+    var = x.var(-1)
+    np.testing.assert_allclose(y.var(-1), var / (var + eps), rtol=1e-12)
+    np.testing.assert_allclose(dit.layernorm(x + 11.0, eps), y, atol=1e-10)          # shift invariance
+    np.testing.assert_allclose(dit.layernorm(x * 4.0, eps / 1e6), dit.layernorm(x, eps / 1e6), atol=1e-6)
+    # a two-element row (a, b) normalises to (+-1) up to eps
+    np.testing.assert_allclose(dit.layernorm(np.array([[1.0, 3.0]]), 0.0), [[-1.0, 1.0]], atol=1e-15)
+
+
+def test_modulate_and_silu_values():
+    u = np.array([1.0, -2.0])
+    np.testing.assert_allclose(dit.modulate(u, np.array([0.5, 0.5]), np.array([1.0, -1.0])), [2.5, 0.5])
+    np.testing.assert_allclose(dit.silu(np.array([0.0, 1.0, -1.0])),
+                               [0.0, 1 / (1 + math.exp(-1)), -1 / (1 + math.exp(1))], atol=1e-15)
+
+
+def test_gelu_tanh_identities():
+    x = np.linspace(-6, 6, 101)
+    g = dit.gelu_tanh(x)
+    np.testing.assert_allclose(g - dit.gelu_tanh(-x), x, atol=1e-12)     # gelu(x) - gelu(-x) = x
+    assert dit.gelu_tanh(np.array([0.0]))[0] == 0.0
+    np.testing.assert_allclose(dit.gelu_tanh(np.array([30.0, -30.0])), [30.0, 0.0], atol=1e-12)
+    # tanh form, not erf form: value at 1 is 0.841192 (erf form: 0.841345)
+    np.testing.assert_allclose(dit.gelu_tanh(np.array([1.0]))[0], 0.8411919906082768, atol=1e-12)
+    # same formula, typed again term by term
+    xv = 0.7
+    want = 0.5 * xv * (1 + math.tanh(0.7978845608028654 * (xv + 0.044715 * xv ** 3)))
+    np.testing.assert_allclose(dit.gelu_tanh(np.array([xv]))[0], want, atol=1e-15)
+
+
+def test_timestep_embedding_pins():
+    e0 = dit.timestep_embedding(0, 256)
+    np.testing.assert_array_equal(e0, np.concatenate([np.ones(128), np.zeros(128)]))
+    for t in (1, 20, 500, 980):
+        e = dit.timestep_embedding(t, 256)
+        np.testing.assert_allclose((e * e).sum(), 128.0, rtol=1e-12)
+        assert e[0] == pytest.approx(math.cos(t)) and e[128] == pytest.approx(math.sin(t))
+        assert e[64] == pytest.approx(math.cos(t * 10000 ** -0.5))
+        assert e[255] == pytest.approx(math.sin(t * 10000 ** (-127 / 128)))
+
+
+def test_positional_embedding_pins():
+    T, gh, gw, D = 3, 2, 5, 16
+    pos = dit.positional_embedding(T, gh, gw, D)
+    assert pos.shape == (T, gh * gw, D)
+    # token (t=0, h'=0, w'=0): temporal = spatial = [0..0 | 1..1] pattern
+    np.testing.assert_allclose(pos[0, 0], np.r_[np.zeros(4), np.ones(4), np.zeros(4), np.ones(4)]
+                               + np.r_[np.zeros(8), np.ones(8)], atol=1e-15)
+    # explicit element: t=2, h'=1, w'=3 -> s = 1*5+3
+    t, hp, wp = 2, 1, 3
+    s = hp * gw + wp
+    q = D // 4                       # frequencies per spatial half-of-half
+    for i in range(q):
+        w_sp = 10000 ** (-i / q)
+        w_t = 10000 ** (-i / (D // 2))
+        assert pos[t, s, i] == pytest.approx(math.sin(hp * w_sp) + math.sin(t * w_t))
+        assert pos[t, s, q + i] == pytest.approx(math.cos(hp * w_sp) + math.sin(t * 10000 ** (-(q + i) / (D // 2))))
+        assert pos[t, s, 2 * q + i] == pytest.approx(math.sin(wp * w_sp) + math.cos(t * w_t))
+        assert pos[t, s, 3 * q + i] == pytest.approx(
+            math.cos(wp * w_sp) + math.cos(t * 10000 ** (-(q + i) / (D // 2))))
+
+
+def test_patchify_layout_and_round_trip():
+    T, H, W, C, p = 2, 4, 6, 3, 2
+    lat = RNG.standard_normal((T, H, W, C))
+    tok = dit.patchify(lat, p)
+    assert tok.shape == (T * 2 * 3, p * p * C)
+    for t in range(T):
+        for hp in range(H // p):
+            for wp in range(W // p):
+                n = (t * (H // p) + hp) * (W // p) + wp
+                for dh in range(p):
+                    for dw in range(p):
+                        for c in range(C):
+                            assert tok[n, (dh * p + dw) * C + c] == lat[t, hp * p + dh, wp * p + dw, c]
+    np.testing.assert_array_equal(dit.unpatchify(tok, T, H, W, C, p), lat)
+
+
+# --------------------------------------------------------------------------- whole network
+
+def _tiny(**kw):
+    base = synth.WORKLOADS["cfg1"].model
+    return replace(base, **kw)
+
+
+def test_identity_patch_embed_round_trip_through_network_ends():
+    """hidden = p*p*C, identity patch weights, depth 0: forward reduces to
+    LN+modulate+head of (patches + pos); with f_w = I and zero modulation the
+    output is the un-patchified LayerNorm of those rows."""
+    cfg = _tiny(hidden=16, heads=4, depth=0, text_dim=16)
+    W = synth.make_weights(cfg, 1)
+    W["p_w"] = np.eye(16, dtype=np.float32); W["p_b"][:] = 0
+    W["f_mod_w"][:] = 0; W["f_mod_b"][:] = 0
+    W["f_w"] = np.eye(16, dtype=np.float32); W["f_b"][:] = 0
+    lat = synth.make_latent(cfg, 2)[0]
+    txt = synth.make_text(cfg, 3)[0]
+    got = dit.forward(cfg, W, lat, txt, 500)
+    rows = dit.patchify(lat.astype(np.float64), 2) + dit.positional_embedding(4, 4, 4, 16).reshape(-1, 16)
+    want = dit.unpatchify(dit.layernorm(rows, cfg.ln_eps), 4, 8, 8, 4, 2)
+    np.testing.assert_allclose(got, want, atol=1e-12)
+
+
+def test_zero_modulation_block_is_identity_plus_cross_attention():
+    cfg = _tiny()
+    W = synth.make_weights(cfg, 5)
+    W["blk0.mod_w"][:] = 0; W["blk0.mod_b"][:] = 0            # all gates 0
+    W2 = dict(W)
+    for k in ("blk0.x_proj_w", "blk0.x_proj_b"):
+        W2[k] = np.zeros_like(W[k])                            # and no cross-attention output
+    cfg0 = replace(cfg, depth=0)
+    W0 = {k: v for k, v in W.items() if not k.startswith("blk0.")}
+    lat = synth.make_latent(cfg, 6)[0]; txt = synth.make_text(cfg, 7)[0]
+    np.testing.assert_allclose(dit.forward(cfg, W2, lat, txt, 500), dit.forward(cfg0, W0, lat, txt, 500), atol=1e-14)
+    # with cross-attention on, the block differs from identity
+    assert np.abs(dit.forward(cfg, W, lat, txt, 500) - dit.forward(cfg0, W0, lat, txt, 500)).max() > 1e-6
+
+
+def test_spatial_and_temporal_attention_locality():
+    """Spatial attention only mixes tokens of one frame; temporal only tokens at one
+    spatial index.  Checked on a block whose other branches are switched off."""
+    cfg = _tiny()
+    D = cfg.hidden
+    lat = synth.make_latent(cfg, 8)[0]; txt = synth.make_text(cfg, 9)[0]
+    lat2 = lat.copy(); lat2[1] += 1.0                          # change frame 1 only
+
+    def run(keep):
+        W = synth.make_weights(cfg, 10)
+        W["blk0.mod_w"][:] = 0
+        b = np.zeros(9 * D, dtype=np.float32); b[keep * 3 * D + 2 * D: keep * 3 * D + 3 * D] = 1.0   # one gate = 1
+        W["blk0.mod_b"] = b
+        W["blk0.x_proj_w"][:] = 0; W["blk0.x_proj_b"][:] = 0
+        W["f_mod_w"][:] = 0; W["f_mod_b"][:] = 0
+        return dit.forward(cfg, W, lat, txt, 500), dit.forward(cfg, W, lat2, txt, 500)
+
+    a, b = run(0)                                              # spatial only
+    assert np.abs(a[1] - b[1]).max() > 1e-3
+    np.testing.assert_allclose(a[[0, 2, 3]], b[[0, 2, 3]], atol=1e-13)
+    a, b = run(1)                                              # temporal only: other frames now change too
+    assert np.abs(a[0] - b[0]).max() > 1e-6
+    # but a change confined to one spatial patch stays in that patch's column of tokens
+    lat3 = lat.copy(); lat3[:, 0:2, 0:2, :] += 1.0
+    W = synth.make_weights(cfg, 10)
+    W["blk0.mod_w"][:] = 0
+    bb = np.zeros(9 * D, dtype=np.float32); bb[3 * D + 2 * D: 3 * D + 3 * D] = 1.0
+    W["blk0.mod_b"] = bb
+    W["blk0.x_proj_w"][:] = 0; W["blk0.x_proj_b"][:] = 0
+    a, b = dit.forward(cfg, W, lat, txt, 500), dit.forward(cfg, W, lat3, txt, 500)
+    np.testing.assert_allclose(a[:, 2:, :, :], b[:, 2:, :, :], atol=1e-13)
+    np.testing.assert_allclose(a[:, :, 2:, :], b[:, :, 2:, :], atol=1e-13)
+    assert np.abs(a[:, 0:2, 0:2] - b[:, 0:2, 0:2]).max() > 1e-3
+
+
+def test_frame_permutation_commutes_with_spatial_branch():
+    cfg = _tiny()
+    D = cfg.hidden
+    W = synth.make_weights(cfg, 15)
+    W["blk0.mod_w"][:] = 0
+    b = np.zeros(9 * D, dtype=np.float32); b[2 * D:3 * D] = 1.0; b[8 * D:] = 1.0     # spatial + MLP gates
+    W["blk0.mod_b"] = b
+    lat = synth.make_latent(cfg, 16)[0]; txt = synth.make_text(cfg, 17)[0]
+    # remove the temporal position term by comparing differences that cancel it:
+    # permuting frames AND their temporal positions is a relabelling, so instead use T-invariant pos
+    perm = np.array([2, 0, 3, 1])
+    out = dit.forward(cfg, W, lat, txt, 500)
+    # undo the temporal embedding by hand: feed frames permuted, expect outputs permuted
+    # only if the temporal position travels with the frame; emulate with a patched pos table
+    orig = dit.positional_embedding
+    try:
+        dit.positional_embedding = lambda T, gh, gw, dim: orig(T, gh, gw, dim)[perm]
+        out_p = dit.forward(cfg, W, lat[perm], txt, 500)
+    finally:
+        dit.positional_embedding = orig
+    np.testing.assert_allclose(out_p, out[perm], atol=1e-12)
+
+
+def test_full3d_block_video_token_permutation_equivariance():
+    """Without positions, permuting video tokens permutes the block's outputs."""
+    cfg = replace(_tiny(), attn_mode=synth.ATTN_FULL3D_CONCAT)
+    W = synth.make_weights(cfg, 18)
+    lat = synth.make_latent(cfg, 19)[0]; txt = synth.make_text(cfg, 20)[0]
+    perm = np.random.default_rng(21).permutation(cfg.video_tokens)
+    orig = dit.positional_embedding
+    try:
+        dit.positional_embedding = lambda T, gh, gw, dim: np.zeros((T, gh * gw, dim))
+        a = dit.patchify(dit.forward(cfg, W, lat, txt, 500), 2)
+        tok = dit.patchify(lat.astype(np.float64), 2)[perm]
+        b = dit.patchify(dit.forward(cfg, W, dit.unpatchify(tok, 4, 8, 8, 4, 2), txt, 500), 2)
+    finally:
+        dit.positional_embedding = orig
+    np.testing.assert_allclose(b, a[perm], atol=1e-12)
+
+
+def test_full3d_row_sampling_equals_full_evaluation():
+    cfg = replace(_tiny(), attn_mode=synth.ATTN_FULL3D_CONCAT)
+    W = synth.make_weights(cfg, 22)
+    lat = synth.make_latent(cfg, 23)[0]; txt = synth.make_text(cfg, 24)[0]
+    full = dit.patchify(dit.forward(cfg, W, lat, txt, 500), 2)
+    rows = np.array([0, 17, 63, 5])
+    np.testing.assert_allclose(dit.forward(cfg, W, lat, txt, 500, video_rows=rows), full[rows], atol=1e-13)
+
+
+# ---- an independent evaluation of the whole tiny network: einsum on [T,S,h,d] tensors,
+# ---- written without looking at the oracle's helper functions.
+
+def _ln(x, eps):
+    m = x.mean(-1, keepdims=True)
+    return (x - m) / np.sqrt(((x - m) ** 2).mean(-1, keepdims=True) + eps)
+
+
+def _sm(s):
+    e = np.exp(s - s.max(-1, keepdims=True))
+    return e / e.sum(-1, keepdims=True)
+
+
+def independent_forward(cfg, W, lat, txt, t):
+    W = {k: v.astype(np.float64) for k, v in W.items()}
+    D, h, T, S, p, C = cfg.hidden, cfg.heads, cfg.frames, cfg.spatial_tokens, cfg.patch, cfg.channels
+    d = D // h
+    gh, gw = cfg.height // p, cfg.width // p
+    fr = np.array([10000.0 ** (-i / 128) for i in range(128)])
+    emb = np.array([math.cos(t * f) for f in fr] + [math.sin(t * f) for f in fr])
+    z = emb @ W["t_w1"] + W["t_b1"]
+    c = (z * (1 / (1 + np.exp(-z)))) @ W["t_w2"] + W["t_b2"]
+    sc = c * (1 / (1 + np.exp(-c)))
+    y = txt.astype(np.float64) @ W["y_w"] + W["y_b"]
+    x = np.zeros((T, gh, gw, D))
+    for tt in range(T):
+        for a in range(gh):
+            for b in range(gw):
+                patch = lat[tt, a * p:(a + 1) * p, b * p:(b + 1) * p, :].astype(np.float64).reshape(-1)
+                pe = np.zeros(D)
+                q4 = D // 4
+                for i in range(q4):
+                    w = 10000.0 ** (-i / q4)
+                    pe[i], pe[q4 + i] = math.sin(a * w), math.cos(a * w)
+                    pe[2 * q4 + i], pe[3 * q4 + i] = math.sin(b * w), math.cos(b * w)
+                for i in range(D // 2):
+                    w = 10000.0 ** (-i / (D // 2))
+                    pe[i] += math.sin(tt * w); pe[D // 2 + i] += math.cos(tt * w)
+                x[tt, a, b] = patch @ W["p_w"] + W["p_b"] + pe
+    x = x.reshape(T, S, D)
+    full3d = cfg.attn_mode == synth.ATTN_FULL3D_CONCAT
+    if full3d:
+        x = np.concatenate([y, x.reshape(T * S, D)])
+    for l in range(cfg.depth):
+        P = f"blk{l}."
+        m = (sc @ W[P + "mod_w"] + W[P + "mod_b"]).reshape(6 if full3d else 9, D)
+        if full3d:
+            u = _ln(x, cfg.ln_eps) * (1 + m[1]) + m[0]
+            qkv = (u @ W[P + "qkv_w"] + W[P + "qkv_b"]).reshape(-1, 3, h, d)
+            pr = _sm(np.einsum("qhd,khd->hqk", qkv[:, 0], qkv[:, 1]) / math.sqrt(d))
+            o = np.einsum("hqk,khd->qhd", pr, qkv[:, 2]).reshape(-1, D)
+            x = x + m[2] * (o @ W[P + "proj_w"] + W[P + "proj_b"])
+            m = np.concatenate([np.zeros((3, D)), m])      # MLP vectors sit at rows 6..8 below
+        else:
+            for name, (i0, eq_s, eq_o) in {"sp": (0, "tqhd,tkhd->thqk", "thqk,tkhd->tqhd"),
+                                            "tm": (3, "qshd,kshd->shqk", "shqk,kshd->qshd")}.items():
+                u = _ln(x, cfg.ln_eps) * (1 + m[i0 + 1]) + m[i0]
+                qkv = (u @ W[P + name + "_qkv_w"] + W[P + name + "_qkv_b"]).reshape(T, S, 3, h, d)
+                pr = _sm(np.einsum(eq_s, qkv[:, :, 0], qkv[:, :, 1]) / math.sqrt(d))
+                o = np.einsum(eq_o, pr, qkv[:, :, 2]).reshape(T, S, D)
+                x = x + m[i0 + 2] * (o @ W[P + name + "_proj_w"] + W[P + name + "_proj_b"])
+            q = (_ln(x, cfg.ln_eps) @ W[P + "x_q_w"] + W[P + "x_q_b"]).reshape(T, S, h, d)
+            kv = (y @ W[P + "x_kv_w"] + W[P + "x_kv_b"]).reshape(-1, 2, h, d)
+            pr = _sm(np.einsum("tshd,lhd->tshl", q, kv[:, 0]) / math.sqrt(d))
+            o = np.einsum("tshl,lhd->tshd", pr, kv[:, 1]).reshape(T, S, D)
+            x = x + o @ W[P + "x_proj_w"] + W[P + "x_proj_b"]
+        u = _ln(x, cfg.ln_eps) * (1 + m[7]) + m[6]
+        hd = u @ W[P + "fc1_w"] + W[P + "fc1_b"]
+        hd = 0.5 * hd * (1 + np.tanh(math.sqrt(2 / math.pi) * (hd + 0.044715 * hd ** 3)))
+        x = x + m[8] * (hd @ W[P + "fc2_w"] + W[P + "fc2_b"])
+    if full3d:
+        x = x[len(y):]
+    fm = sc @ W["f_mod_w"] + W["f_mod_b"]
+    o = (_ln(x, cfg.ln_eps) * (1 + fm[D:]) + fm[:D]) @ W["f_w"] + W["f_b"]
+    o = o.reshape(T, gh, gw, p, p, C)
+    out = np.zeros((T, cfg.height, cfg.width, C))
+    for a in range(gh):
+        for b in range(gw):
+            out[:, a * p:(a + 1) * p, b * p:(b + 1) * p, :] = o[:, a, b]
+    return out
+
+
+@pytest.mark.parametrize("mode", [synth.ATTN_FACTORIZED_CROSS, synth.ATTN_FULL3D_CONCAT])
+@pytest.mark.parametrize("depth,std", [(1, 0.02), (2, 0.3)])
+def test_whole_tiny_network_against_independent_einsum_evaluation(depth, std, mode):
+    cfg = _tiny(depth=depth, attn_mode=mode)
+    W = synth.make_weights(cfg, 31, std=std)          # std 0.3: softmax rows far from uniform
+    lat = synth.make_latent(cfg, 32)[0]; txt = synth.make_text(cfg, 33)[0]
+    got = dit.forward(cfg, W, lat, txt, 500)
+    want = independent_forward(cfg, W, lat, txt, 500)
+    np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-11)
+
+
+def test_fp32_oracle_agrees_with_fp64_oracle():
+    w = synth.WORKLOADS["cfg1"]
+    W = synth.make_weights(w.model, w.weight_seed)
+    lat, cond, _ = synth.workload_inputs(w)
+    a = dit.forward(w.model, W, lat[0], cond[0], 500, dtype=np.float64)
+    b = dit.forward(w.model, W, lat[0], cond[0], 500, dtype=np.float32)
+    assert b.dtype == np.float32
+    assert np.linalg.norm(a - b) / np.linalg.norm(a) < 1e-5
