@@ -1,0 +1,191 @@
+/* flexdenoise.h -- C ABI of the MI355X-native denoising path.
+ *
+ * What the library computes.  FlexCache (arXiv 2501.04012) serves a text-to-video
+ * request either from Gaussian noise or, on a cache hit, from the stored latent of
+ * an earlier request's step k: the stored latent is set as the input and generation
+ * proceeds from the next step (Sec. 2.2 "Caching for Diffusion Models"; Sec. 3.2
+ * "Cache lookup"; Sec. 4.2.2: a step-10 cache lets the request proceed from the
+ * 11th step).  A denoising step takes the current latent and the prompt embedding,
+ * predicts the noise and removes it; steps are sequential and dominate a request's
+ * run time (Sec. 2.1 "Diffusion Model"; Sec. 6.2.1 "Performance Breakdown").  This
+ * library is that step, and the loop over the remaining N-k steps, for a latent
+ * video diffusion transformer.
+ *
+ * The paper fixes neither the network nor the sampler constants; the network here
+ * is a pre-LN adaLN diffusion transformer in two video forms (attn_mode), the
+ * sampler is deterministic DDIM (eta = 0) on a linear-beta schedule with
+ * classifier-free guidance.
+ *
+ * Conventions for every call
+ *   - returns an int status: FC_OK (0) or a negative FC_ERR_*; never throws, never
+ *     aborts, never prints.  fc_last_error() gives a per-thread message.
+ *   - "dev" pointers are HIP device pointers on the current device, "host"
+ *     pointers are ordinary host memory.  The caller owns every buffer it passes;
+ *     the library owns the fc_model and the device copy of the weights.
+ *   - work is enqueued on the given hipStream_t (passed as void*; NULL = the
+ *     default stream) and is NOT synchronised: the caller synchronises the stream.
+ *   - nothing allocates device memory after fc_model_set_weights(); all scratch
+ *     comes from the caller's workspace.
+ *   - one fc_model may be used by one host thread at a time.  Results are
+ *     run-to-run bitwise deterministic (no atomics in any reduction).
+ */
+#ifndef FLEXDENOISE_H
+#define FLEXDENOISE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fc_model fc_model; /* opaque, library-owned */
+
+enum {
+  FC_OK = 0,
+  FC_ERR_NULL = -1,        /* a required pointer is NULL */
+  FC_ERR_SHAPE = -2,       /* inconsistent configuration (divisibility, sizes) */
+  FC_ERR_RANGE = -3,       /* step / k / batch outside its range */
+  FC_ERR_WORKSPACE = -4,   /* workspace smaller than fc_workspace_bytes() */
+  FC_ERR_DEVICE = -5,      /* a HIP call failed */
+  FC_ERR_UNSUPPORTED = -6, /* e.g. eta != 0 */
+  FC_ERR_STATE = -7        /* weights not set yet */
+};
+
+enum { FC_ATTN_FACTORIZED_CROSS = 0, /* spatial attn, temporal attn, text cross-attn per block */
+       FC_ATTN_FULL3D_CONCAT = 1 };  /* one attention over [text ; video] tokens per block */
+enum { FC_F32 = 0,   /* fp32 weights, activations and arithmetic */
+       FC_BF16 = 1 };/* bf16 weights/activations on MFMA, fp32 accumulation, fp32 residual stream */
+
+/* Model shape.  Latent is [frames, height, width, channels]; patches are
+ * patch x patch in space (temporal patch 1), so a frame has
+ * S = (height/patch)*(width/patch) tokens and the video N = frames*S tokens in
+ * (t, h', w') row-major order.  hidden % heads == 0, hidden % 4 == 0,
+ * height % patch == 0, width % patch == 0, t_embed_dim even. */
+typedef struct {
+  int32_t frames, height, width, channels, patch;
+  int32_t hidden, heads, mlp_dim, depth;
+  int32_t text_len, text_dim, t_embed_dim;
+  int32_t attn_mode; /* FC_ATTN_* */
+  int32_t dtype;     /* FC_F32 or FC_BF16 */
+  float ln_eps;      /* LayerNorm epsilon (affine-free, biased variance) */
+} fc_model_config;
+
+/* Sampler.  beta_i linear from beta_start to beta_end over train_steps; the
+ * num_steps sampling timesteps are tau_j = j*(train_steps/num_steps), visited in
+ * descending order; step s (1-based) maps t = tau_{N-s} to tau_{N-s-1}, the last
+ * step to abar_prev = 1.  eta must be 0. */
+typedef struct {
+  int32_t train_steps;
+  float beta_start, beta_end;
+  int32_t num_steps;
+  float guidance_scale; /* used only when null_cond != NULL */
+  float eta;
+} fc_schedule;
+
+/* Create a model for `cfg` on the current device.  *out receives the handle.
+ * Errors: FC_ERR_NULL, FC_ERR_SHAPE, FC_ERR_DEVICE. */
+int fc_model_create(const fc_model_config* cfg, fc_model** out);
+
+/* Number of floats fc_model_set_weights() expects for this model. */
+int fc_model_weight_count(const fc_model* m, size_t* out);
+
+/* Upload all parameters.  host_blob (host, fp32, little-endian) is the
+ * concatenation, in this order, of row-major tensors with linear weights stored
+ * [in, out] (y = x W + b):
+ *   t_w1[te,D] t_b1[D] t_w2[D,D] t_b2[D]   timestep MLP on the sinusoid
+ *   y_w[dt,D] y_b[D]                      text projection
+ *   p_w[p*p*C,D] p_b[D]                   patch embedding (patch feature order dh,dw,c)
+ *   per block, FACTORIZED_CROSS:
+ *     mod_w[D,9D] mod_b[9D]  (shift,scale,gate) x (spatial, temporal, mlp)
+ *     sp_qkv_w[D,3D] b  sp_proj_w[D,D] b  tm_qkv_w[D,3D] b  tm_proj_w[D,D] b
+ *     x_q_w[D,D] b  x_kv_w[D,2D] b  x_proj_w[D,D] b
+ *     fc1_w[D,M] b  fc2_w[M,D] b
+ *   per block, FULL3D_CONCAT:
+ *     mod_w[D,6D] mod_b[6D]  (shift,scale,gate) x (attn, mlp)
+ *     qkv_w[D,3D] b  proj_w[D,D] b  fc1_w[D,M] b  fc2_w[M,D] b
+ *   f_mod_w[D,2D] f_mod_b[2D]  (shift,scale) of the final layer
+ *   f_w[D,p*p*C] f_b[p*p*C]
+ * qkv columns are [q | k | v], each split into `heads` consecutive groups.
+ * The blob is copied (and rounded to bf16, nearest-even, for FC_BF16); the caller
+ * may free it on return.  This call allocates device memory and synchronises.
+ * Errors: FC_ERR_NULL, FC_ERR_SHAPE (n_floats mismatch), FC_ERR_DEVICE. */
+int fc_model_set_weights(fc_model* m, const float* host_blob, size_t n_floats);
+
+/* Free the model and its device memory.  NULL is accepted. */
+int fc_model_destroy(fc_model* m);
+
+/* Bytes of device workspace a step/resume call needs for `batch_requests`
+ * requests, with (use_cfg != 0) or without a guidance pair. */
+int fc_workspace_bytes(const fc_model* m, int32_t batch_requests, int32_t use_cfg, size_t* out);
+
+/* One denoising step (Sec. 2.1): latent <- DDIM update of latent with the guided
+ * noise estimate, for the step-th (1-based) of sched->num_steps steps.
+ *   latent     dev, fp32 [R, frames, height, width, channels], updated in place
+ *   cond       dev, fp32 [R, text_len, text_dim], prompt embeddings
+ *   null_cond  dev, fp32 [text_len, text_dim] shared 'empty prompt' embedding, or
+ *              NULL for no classifier-free guidance
+ *   eps_out    dev, fp32, same shape as latent, receives the (guided) noise
+ *              estimate; may be NULL
+ * Errors: FC_ERR_NULL, FC_ERR_STATE, FC_ERR_RANGE (step not in 1..N, R < 1),
+ * FC_ERR_UNSUPPORTED (eta != 0), FC_ERR_WORKSPACE, FC_ERR_DEVICE. */
+int fc_denoise_step(fc_model* m, float* latent, const float* cond, const float* null_cond,
+                    const fc_schedule* sched, int32_t step, int32_t batch_requests,
+                    float* eps_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Cache-hit resume (Sec. 2.2; Sec. 3.2 "Cache lookup"; Sec. 4.2.2): `latent`
+ * holds the stored latents after step k; runs steps k+1 .. N in place.  k = 0 is
+ * a full generation from noise, k = N returns at once.  All R requests share k.
+ * Work that does not depend on the timestep (text projection, cross-attention
+ * keys/values) is done once per call.  Arguments and errors as fc_denoise_step,
+ * with FC_ERR_RANGE for k outside 0..N. */
+int fc_denoise_resume(fc_model* m, float* latent, const float* cond, const float* null_cond,
+                      const fc_schedule* sched, int32_t k, int32_t batch_requests,
+                      void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The four DDIM coefficients of a step, as the kernels receive them (computed in
+ * double, rounded to float): out4 = { sqrt(abar_t), sqrt(1-abar_t), sqrt(abar_prev),
+ * sqrt(1-abar_prev) }, *t_out = training timestep of the step.  Host only. */
+int fc_schedule_coefficients(const fc_schedule* sched, int32_t step, float* out4, int32_t* t_out);
+
+const char* fc_status_string(int status);
+const char* fc_last_error(void);
+
+/* ---- single operators of the step, exposed for per-kernel tests and timing.
+ * All pointers dev; dtype FC_F32 -> float elements, FC_BF16 -> bfloat16 (uint16)
+ * elements for every tensor marked "act". ------------------------------------- */
+
+/* out[M,N] (act) = epilogue(A[M,K] (act) * Wt[N,K]^T (act) + bias[N] (f32)).
+ * epilogue 0: bias only; 1: bias + GELU(tanh).  The network's linear layers. */
+int fc_op_linear(int32_t dtype, const void* A, const void* Wt, const float* bias, void* out,
+                 int32_t M, int32_t N, int32_t K, int32_t epilogue, void* hip_stream);
+
+/* x[M,N] (f32) += gate[N] (f32, NULL = ones) * (A[M,K] * Wt[N,K]^T + bias[N]):
+ * the gated residual epilogue of the out-projection and fc2 layers. */
+int fc_op_linear_residual(int32_t dtype, const void* A, const void* Wt, const float* bias,
+                          const float* gate, float* x, int32_t M, int32_t N, int32_t K,
+                          void* hip_stream);
+
+/* Unmasked softmax(q k^T / sqrt(d)) v for G independent problems (one per
+ * sequence and head).  q [G, nq, d], k [G, nk, d] (act), vt [G, d, nk_pad] (act,
+ * V transposed, nk_pad = nk rounded up to 64, padding ignored), out [G, nq, d]
+ * (act).  impl 0: library's choice, 1: force the plain (non-MFMA) kernel. */
+int fc_op_attention(int32_t dtype, const void* q, const void* k, const void* vt, void* out,
+                    int32_t G, int32_t nq, int32_t nk, int32_t d, int32_t impl, void* hip_stream);
+
+/* out[M,D] (act) = LayerNorm(x[M,D] (f32)) * (1 + scale[D]) + shift[D]
+ * (shift/scale f32, both NULL = plain LayerNorm); eps as in the model config. */
+int fc_op_layernorm_modulate(int32_t dtype, const float* x, const float* shift, const float* scale,
+                             void* out, int32_t M, int32_t D, float eps, void* hip_stream);
+
+/* Fused guidance + DDIM update on n elements per request, R requests:
+ * eps = eps_u + s (eps_c - eps_u) (eps_u NULL: eps = eps_c);
+ * x <- c[2] * (x - c[1] eps) / c[0] + c[3] eps, c = fc_schedule_coefficients.
+ * eps_out (NULL allowed) receives eps. */
+int fc_op_cfg_ddim(float* x, const float* eps_c, const float* eps_u, float* eps_out, size_t n_total,
+                   float guidance_scale, const float* coef4_host, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXDENOISE_H */

@@ -1,0 +1,403 @@
+// Unmasked softmax(q k^T / sqrt(d)) v.
+//   k_attn_plain : one thread per query row, online softmax in fp32.  Any dtype, any
+//                  strides; used by the fp32 configuration and as the fallback.
+//   k_attn_flash : bf16 MFMA flash kernel.  Scores are computed transposed
+//                  (S^T = K Q^T) so that each query column lives in two lanes, the
+//                  running max / sum need one cross-lane exchange per tile, and the
+//                  probabilities are already in the register layout the P V MFMA
+//                  takes as its B operand: P never touches LDS.
+#include "common.h"
+
+namespace fc {
+
+__device__ __forceinline__ int key_batch(const AttnParams& p, int b) {
+  return (p.kv_shared_tail && b >= p.kv_split) ? p.kv_split : b;
+}
+
+// ---------------------------------------------------------------- plain kernel
+template <typename T, int HD>
+__global__ __launch_bounds__(64) void k_attn_plain(AttnParams p) {
+  const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long total = (long long)p.B * p.heads * p.groups * p.nq;
+  if (gid >= total) return;
+  const int i = (int)(gid % p.nq);
+  long long r = gid / p.nq;
+  const int g = (int)(r % p.groups); r /= p.groups;
+  const int head = (int)(r % p.heads);
+  const int b = (int)(r / p.heads);
+  const int kb = key_batch(p, b);
+
+  const int qtok = g * p.q_gstride + i * p.q_istride;
+  const T* q = (const T*)p.q + (((size_t)b * p.heads + head) * p.q_tokens + qtok) * HD;
+  const T* kbase = (const T*)p.k + ((size_t)kb * p.heads + head) * (size_t)p.k_tokens * HD;
+  const T* vbase = (const T*)p.vt + ((size_t)kb * p.heads + head) * (size_t)HD * p.k_tokens_pad;
+
+  float qv[HD], o[HD];
+#pragma unroll
+  for (int c = 0; c < HD; ++c) { qv[c] = to_f32(q[c]); o[c] = 0.0f; }
+  float m = -INFINITY, l = 0.0f;
+  for (int j = 0; j < p.nk; ++j) {
+    const int ktok = g * p.k_gstride + j * p.k_istride;
+    const T* kr = kbase + (size_t)ktok * HD;
+    float s = 0.0f;
+#pragma unroll
+    for (int c = 0; c < HD; ++c) s += qv[c] * to_f32(kr[c]);
+    s *= p.scale_log2;
+    const float mn = fmaxf(m, s);
+    const float alpha = exp2f(m - mn);     // m = -inf on the first key: exp2(-inf) = 0
+    const float pj = exp2f(s - mn);
+    l = l * alpha + pj;
+#pragma unroll
+    for (int c = 0; c < HD; ++c) o[c] = o[c] * alpha + pj * to_f32(vbase[(size_t)c * p.k_tokens_pad + ktok]);
+    m = mn;
+  }
+  const float inv = 1.0f / l;
+  T* out = (T*)p.out + ((size_t)b * p.q_tokens + qtok) * ((size_t)p.heads * HD) + (size_t)head * HD;
+#pragma unroll
+  for (int c = 0; c < HD; ++c) out[c] = from_f32<T>(o[c] * inv);
+}
+
+template <typename T, int HD>
+static hipError_t run_plain(const AttnParams& p, hipStream_t s) {
+  long long total = (long long)p.B * p.heads * p.groups * p.nq;
+  if (total == 0) return hipSuccess;
+  k_attn_plain<T, HD><<<(unsigned)((total + 63) / 64), 64, 0, s>>>(p);
+  return hipGetLastError();
+}
+
+template <typename T>
+static hipError_t dispatch_plain(const AttnParams& p, hipStream_t s) {
+  switch (p.hd) {
+    case 8: return run_plain<T, 8>(p, s);
+    case 16: return run_plain<T, 16>(p, s);
+    case 32: return run_plain<T, 32>(p, s);
+    case 64: return run_plain<T, 64>(p, s);
+    case 72: return run_plain<T, 72>(p, s);
+    case 96: return run_plain<T, 96>(p, s);
+    case 128: return run_plain<T, 128>(p, s);
+  }
+  return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------- flash kernel (bf16, MFMA)
+// Workgroup = 4 waves; wave w owns query rows [64w, 64w+64) of a 256-row query tile
+// (two 32-column MFMA tiles qt).  Keys are walked in tiles of 64, staged in LDS as
+// K [64][HDP] and V^T [HDV][64] (double-buffered, register-prefetched).
+//
+// Per key tile and wave:
+//   S^T[a][qt] (32 keys x 32 queries) = K_a (A operand) x Q_qt^T (B operand, in
+//   registers for the whole kernel), contraction over the head dim in steps of 16.
+//   Lane (i, h) of S^T holds query column i and key rows r = 8g + 4h + e.  The K row
+//   fed as MFMA row r is key perm(r) = r with bits 2 and 3 swapped, so that the 8
+//   values of registers {4(2s), .., 4(2s+1)+3} are the 8 consecutive keys
+//   16s + 8h .. + 7: exactly one 16-byte read of V^T for the P V step.
+//   O^T[c][qt] (32 head dims x 32 queries) += V^T_c (A operand) x P^T (B operand).
+//
+// HD = true head dim; HDP = HD rounded up to 16 (contraction of Q K^T); HDV = HD
+// rounded up to 32 (rows of O^T).  Pad lanes are zero-filled when staged.
+template <int HD>
+struct FlashCfg {
+  static constexpr int HDP = (HD + 15) / 16 * 16;
+  static constexpr int HDV = (HD + 31) / 32 * 32;
+  static constexpr int KS = HDP / 16;        // k-steps of Q K^T
+  static constexpr int CT = HDV / 32;        // O^T row tiles
+  static constexpr int LDK = HDP + 8;        // LDS row of K tile (elements)
+  static constexpr int LDV = 64 + 8;         // LDS row of V^T tile
+  static constexpr int K_ELEMS = 64 * LDK, V_ELEMS = HDV * LDV;
+  static constexpr size_t SMEM = (size_t)2 * (K_ELEMS + V_ELEMS) * sizeof(bf16_t);
+  static constexpr int CH = HD / 8;          // 16-byte chunks per K row
+  static constexpr int K_CHUNKS = 64 * CH;   // per tile
+  static constexpr int V_CHUNKS = HD * 8;    // HD rows x 8 chunks of 8 keys
+};
+
+template <int HD>
+__global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnParams p) {
+  using C = FlashCfg<HD>;
+  static_assert(HD % 8 == 0, "head dim must be a multiple of 8");
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  bf16_t* Ks = (bf16_t*)smem_raw;                 // [2][64][LDK]
+  bf16_t* Vs = Ks + 2 * C::K_ELEMS;               // [2][HDV][LDV]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 31, lh = lane >> 5;
+
+  // problem and query tile of this workgroup
+  const int qtiles = (p.nq + 255) / 256;
+  int bid = blockIdx.x;
+  const int qtile = bid % qtiles; bid /= qtiles;
+  const int g = bid % p.groups; bid /= p.groups;
+  const int head = bid % p.heads;
+  const int b = bid / p.heads;
+  const int kb = key_batch(p, b);
+
+  const bf16_t* qbase = (const bf16_t*)p.q + ((size_t)b * p.heads + head) * (size_t)p.q_tokens * HD;
+  const bf16_t* kbase = (const bf16_t*)p.k + (((size_t)kb * p.heads + head) * (size_t)p.k_tokens +
+                                              (size_t)g * p.k_gstride) * HD;
+  const bf16_t* vbase = (const bf16_t*)p.vt + ((size_t)kb * p.heads + head) * (size_t)HD * p.k_tokens_pad +
+                        (size_t)g * p.k_gstride;
+
+  // ---- Q fragments: B operand, lane (i, h) holds Q[row i][16s + 8h .. +7]
+  bf16x8 qf[2][C::KS];
+  const int q0 = qtile * 256 + wave * 64;
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    int qi = q0 + qt * 32 + li;
+    qi = qi < p.nq ? qi : p.nq - 1;
+    const bf16_t* qr = qbase + (size_t)(g * p.q_gstride + qi) * HD;
+#pragma unroll
+    for (int s = 0; s < C::KS; ++s) {
+      const int c0 = s * 16 + lh * 8;
+      bf16x8 v;
+      if (c0 + 8 <= HD) v = *(const bf16x8*)(qr + c0);
+      else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (bf16_t)0.0f;
+      }
+      qf[qt][s] = v;
+    }
+  }
+
+  f32x16 oacc[C::CT][2];
+#pragma unroll
+  for (int c = 0; c < C::CT; ++c)
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[c][qt][r] = 0.0f;
+  float mrow[2] = {-INFINITY, -INFINITY};   // running max (raw scores) of this lane's query column
+  float lrow[2] = {0.0f, 0.0f};             // this lane's partial sum (its 32 of the 64 keys per tile)
+
+  // ---- staging
+  constexpr int KPT = (C::K_CHUNKS + 255) / 256, VPT = (C::V_CHUNKS + 255) / 256;
+  bf16x8 rk[KPT], rv[VPT];
+  const int nkt = (p.nk + 63) / 64;
+
+  auto gload = [&](int kt) {
+    const int j0 = kt * 64;
+#pragma unroll
+    for (int c = 0; c < KPT; ++c) {
+      int ch = tid + c * 256;
+      if (ch < C::K_CHUNKS) {
+        int row = ch / C::CH, kc = ch % C::CH;
+        int j = j0 + row; j = j < p.nk ? j : p.nk - 1;          // keys past nk are masked later
+        rk[c] = *(const bf16x8*)(kbase + (size_t)j * HD + kc * 8);
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < VPT; ++c) {
+      int ch = tid + c * 256;
+      if (ch < C::V_CHUNKS) {
+        int row = ch / 8, jc = ch % 8;
+        int j = j0 + jc * 8;
+        bf16x8 v = *(const bf16x8*)(vbase + (size_t)row * p.k_tokens_pad + j);   // inside the padded row
+        if (j + 8 > p.nk) {                                      // padding may hold anything: zero it
+#pragma unroll
+          for (int e = 0; e < 8; ++e) if (j + e >= p.nk) v[e] = (bf16_t)0.0f;
+        }
+        rv[c] = v;
+      }
+    }
+  };
+  auto sstore = [&](int buf) {
+    bf16_t* ks = Ks + buf * C::K_ELEMS;
+    bf16_t* vs = Vs + buf * C::V_ELEMS;
+#pragma unroll
+    for (int c = 0; c < KPT; ++c) {
+      int ch = tid + c * 256;
+      if (ch < C::K_CHUNKS) {
+        int row = ch / C::CH, kc = ch % C::CH;
+        *(bf16x8*)(ks + row * C::LDK + kc * 8) = rk[c];
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < VPT; ++c) {
+      int ch = tid + c * 256;
+      if (ch < C::V_CHUNKS) {
+        int row = ch / 8, jc = ch % 8;
+        *(bf16x8*)(vs + row * C::LDV + jc * 8) = rv[c];
+      }
+    }
+  };
+
+  // zero the pad columns of K (head dims HD..HDP) and pad rows of V^T (HD..HDV) once, both buffers
+  if constexpr (C::HDP != HD) {
+    for (int i = tid; i < 2 * 64 * (C::HDP - HD); i += 256) {
+      int buf = i / (64 * (C::HDP - HD)), r = i % (64 * (C::HDP - HD));
+      Ks[buf * C::K_ELEMS + (r / (C::HDP - HD)) * C::LDK + HD + r % (C::HDP - HD)] = (bf16_t)0.0f;
+    }
+  }
+  if constexpr (C::HDV != HD) {
+    for (int i = tid; i < 2 * (C::HDV - HD) * 64; i += 256) {
+      int buf = i / ((C::HDV - HD) * 64), r = i % ((C::HDV - HD) * 64);
+      Vs[buf * C::V_ELEMS + (HD + r / 64) * C::LDV + r % 64] = (bf16_t)0.0f;
+    }
+  }
+
+  gload(0);
+  sstore(0);
+  __syncthreads();
+
+  const int prow = (li & 0x13) | ((li & 4) << 1) | ((li & 8) >> 1);   // li with bits 2 and 3 swapped
+  const float cs = p.scale_log2;
+
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nkt) gload(kt + 1);
+    const bf16_t* ks = Ks + buf * C::K_ELEMS;
+    const bf16_t* vs = Vs + buf * C::V_ELEMS;
+
+    // ---- S^T = K Q^T
+    f32x16 sacc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[a][qt][r] = 0.0f;
+#pragma unroll
+    for (int s = 0; s < C::KS; ++s) {
+      bf16x8 kf[2];
+#pragma unroll
+      for (int a = 0; a < 2; ++a) kf[a] = *(const bf16x8*)(ks + (a * 32 + prow) * C::LDK + s * 16 + lh * 8);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt)
+          sacc[a][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[a], qf[qt][s], sacc[a][qt], 0, 0, 0);
+    }
+
+    // ---- mask keys past nk (last tile only).  Register 4g+e of tile a is key
+    //      32a + 16(g/2) + 8h + 4(g%2) + e of this tile.
+    if (kt == nkt - 1 && (p.nk & 63) != 0) {
+      const int rem = p.nk - kt * 64;
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            int key = 32 * a + 16 * (gg >> 1) + 8 * lh + 4 * (gg & 1) + e;
+            if (key >= rem) { sacc[a][0][4 * gg + e] = -INFINITY; sacc[a][1][4 * gg + e] = -INFINITY; }
+          }
+    }
+
+    // ---- online softmax per query column, P packed to bf16 in B-operand order
+    bf16x8 pf[2][2][2];       // [qt][a][s2]
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+      float mx = sacc[0][qt][0];
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[a][qt][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mn = fmaxf(mrow[qt], mx);          // finite: every tile has at least one valid key
+      const float alpha = __builtin_amdgcn_exp2f((mrow[qt] - mn) * cs);
+      mrow[qt] = mn;
+      const float mc = mn * cs;
+      float sum = 0.0f;
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          bf16x8 pk;
+#pragma unroll
+          for (int x = 0; x < 8; ++x) {
+            float pv = __builtin_amdgcn_exp2f(sacc[a][qt][8 * s2 + x] * cs - mc);
+            sum += pv;
+            pk[x] = (bf16_t)pv;
+          }
+          pf[qt][a][s2] = pk;
+        }
+      lrow[qt] = lrow[qt] * alpha + sum;
+#pragma unroll
+      for (int c = 0; c < C::CT; ++c)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[c][qt][r] *= alpha;
+    }
+
+    // ---- O^T += V^T P^T
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        bf16x8 vf[C::CT];
+#pragma unroll
+        for (int c = 0; c < C::CT; ++c)
+          vf[c] = *(const bf16x8*)(vs + (c * 32 + li) * C::LDV + a * 32 + s2 * 16 + lh * 8);
+#pragma unroll
+        for (int c = 0; c < C::CT; ++c)
+#pragma unroll
+          for (int qt = 0; qt < 2; ++qt)
+            oacc[c][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c], pf[qt][a][s2], oacc[c][qt], 0, 0, 0);
+      }
+
+    if (kt + 1 < nkt) sstore(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- finish: O / l, write token-major.  Lane (i, h) holds query column i, head
+  //      dims 32c + 8g + 4h + e in register 4g + e.
+  bf16_t* obase = (bf16_t*)p.out + (size_t)b * p.q_tokens * ((size_t)p.heads * HD) + (size_t)head * HD;
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt) {
+    const float ltot = lrow[qt] + __shfl_xor(lrow[qt], 32, 64);
+    const float inv = 1.0f / ltot;
+    const int qi = q0 + qt * 32 + li;
+    if (qi < p.nq) {
+      bf16_t* orow = obase + (size_t)(g * p.q_gstride + qi) * ((size_t)p.heads * HD);
+#pragma unroll
+      for (int c = 0; c < C::CT; ++c)
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) {
+          const int dd = 32 * c + 8 * gg + 4 * lh;
+          if (dd < HD) {
+            bf16x4 ov;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)(oacc[c][qt][4 * gg + e] * inv);
+            *(bf16x4*)(orow + dd) = ov;
+          }
+        }
+    }
+  }
+}
+
+template <int HD>
+static hipError_t run_flash(const AttnParams& p, hipStream_t s) {
+  using C = FlashCfg<HD>;
+  auto kern = k_attn_flash<HD>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::SMEM);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  long long blocks = (long long)p.B * p.heads * p.groups * ((p.nq + 255) / 256);
+  if (blocks == 0) return hipSuccess;
+  kern<<<(unsigned)blocks, 256, C::SMEM, s>>>(p);
+  return hipGetLastError();
+}
+
+// The flash kernel needs unit-stride tokens inside a group, 16-byte aligned rows
+// and group starts, and head dims it is instantiated for.
+static bool flash_ok(const AttnParams& p) {
+  if (p.hd != 64 && p.hd != 72) return false;
+  if (p.q_istride != 1 || p.k_istride != 1) return false;
+  if (p.nk < 1 || p.nq < 1) return false;
+  if ((p.k_gstride % 8) != 0 || (p.k_tokens_pad % 8) != 0) return false;
+  if ((((uintptr_t)p.q | (uintptr_t)p.k | (uintptr_t)p.vt | (uintptr_t)p.out) & 15) != 0) return false;
+  // the last V^T tile read of a group must stay inside the padded row
+  if ((long long)(p.groups - 1) * p.k_gstride + (long long)((p.nk + 63) / 64) * 64 > p.k_tokens_pad) return false;
+  return true;
+}
+
+hipError_t launch_attention(int bf16, const AttnParams& p, int impl, hipStream_t s) {
+  if (!bf16) return dispatch_plain<float>(p, s);
+  if (impl == 0 && flash_ok(p)) {
+    if (p.hd == 64) return run_flash<64>(p, s);
+    if (p.hd == 72) return run_flash<72>(p, s);
+  }
+  return dispatch_plain<bf16_t>(p, s);
+}
+
+}  // namespace fc

@@ -1,0 +1,188 @@
+// Shared device/host helpers of the denoising library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+namespace fc {
+
+typedef __bf16 bf16_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+__device__ __forceinline__ float silu_f(float v) { return v / (1.0f + __expf(-v)); }
+
+// GELU, tanh form.  tanh(u) = 1 - 2/(exp(2u)+1) stays finite for large |u|.
+__device__ __forceinline__ float gelu_tanh_f(float v) {
+  const float c = 0.7978845608028654f;
+  float u = c * (v + 0.044715f * v * v * v);
+  float t = 1.0f - 2.0f / (__expf(2.0f * u) + 1.0f);
+  return 0.5f * v * (1.0f + t);
+}
+
+inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+inline size_t round_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
+
+// ---------------------------------------------------------------- GEMM epilogues
+// Every GEMM kernel hands its accumulators to an epilogue as groups of four
+// consecutive rows (m0..m0+3) of one column n, the natural unit of the 32x32 MFMA
+// accumulator layout.  `Mvalid` bounds rows, `Nvalid` bounds columns.
+
+enum EpiMode : int {
+  EPI_STORE = 0,     // out[m,n] = acc + bias
+  EPI_GELU = 1,      // out[m,n] = gelu(acc + bias)
+  EPI_RESID = 2,     // x[m,n] += gate[n] * (acc + bias)     (gate NULL: 1)
+  EPI_HEADS = 3,     // scatter into per-head q / k / v^T tensors
+  EPI_UNPATCH = 4    // scatter token rows back into a latent-shaped fp32 tensor
+};
+
+struct EpiParams {
+  const float* bias = nullptr;   // [N]
+  void* out = nullptr;           // EPI_STORE / EPI_GELU: act [M, ldo]
+  int ldo = 0;
+  float* x = nullptr;            // EPI_RESID: fp32 [M, ldo]
+  const float* gate = nullptr;   // EPI_RESID: [N] or NULL
+  // EPI_HEADS: column n -> which = which0 + n / D (0 q, 1 k, 2 v), head = (n % D) / hd.
+  // Row m -> (b, tok) = (m / tokens, m % tokens).
+  // q, k: [b, head, tok, hd];  vt: [b, head, hd, tokens_pad].
+  void* q = nullptr; void* k = nullptr; void* vt = nullptr;
+  int which0 = 0, D = 0, heads = 0, hd = 0, tokens = 0, tokens_pad = 0;
+  // EPI_UNPATCH: row m -> (b, t, h', w'), column f -> (dh, dw, c); eps [b, T, H, W, C]
+  float* eps = nullptr;
+  int T = 0, H = 0, W = 0, C = 0, p = 0;
+};
+
+template <typename T, int MODE>
+struct Epilogue {
+  EpiParams P;
+  int Mvalid, Nvalid;
+
+  __device__ __forceinline__ void store4(int m0, int n, const float (&acc)[4]) const {
+    if (n >= Nvalid || m0 >= Mvalid) return;
+    const float b = P.bias ? P.bias[n] : 0.0f;
+    if constexpr (MODE == EPI_STORE || MODE == EPI_GELU) {
+      T* o = (T*)P.out;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (m0 + e < Mvalid) {
+          float v = acc[e] + b;
+          if constexpr (MODE == EPI_GELU) v = gelu_tanh_f(v);
+          o[(size_t)(m0 + e) * P.ldo + n] = from_f32<T>(v);
+        }
+      }
+    } else if constexpr (MODE == EPI_RESID) {
+      const float g = P.gate ? P.gate[n] : 1.0f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (m0 + e < Mvalid) {
+          size_t idx = (size_t)(m0 + e) * P.ldo + n;
+          P.x[idx] = P.x[idx] + g * (acc[e] + b);
+        }
+      }
+    } else if constexpr (MODE == EPI_HEADS) {
+      const int which = P.which0 + n / P.D;
+      const int c = n % P.D;
+      const int head = c / P.hd, dd = c % P.hd;
+      if (which < 2) {
+        T* dst = (T*)(which == 0 ? P.q : P.k);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          int m = m0 + e;
+          if (m < Mvalid) {
+            int bb = m / P.tokens, tok = m % P.tokens;
+            dst[(((size_t)bb * P.heads + head) * P.tokens + tok) * P.hd + dd] = from_f32<T>(acc[e] + b);
+          }
+        }
+      } else {
+        T* dst = (T*)P.vt;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          int m = m0 + e;
+          if (m < Mvalid) {
+            int bb = m / P.tokens, tok = m % P.tokens;
+            dst[(((size_t)bb * P.heads + head) * P.hd + dd) * P.tokens_pad + tok] = from_f32<T>(acc[e] + b);
+          }
+        }
+      }
+    } else if constexpr (MODE == EPI_UNPATCH) {
+      const int gw = P.W / P.p, gh = P.H / P.p;
+      const int S = gw * gh;
+      const int dh = n / (P.p * P.C), dw = (n / P.C) % P.p, c = n % P.C;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        int m = m0 + e;
+        if (m < Mvalid) {
+          int bb = m / (P.T * S), r = m % (P.T * S);
+          int t = r / S, s = r % S;
+          int hp = s / gw, wp = s % gw;
+          size_t idx = ((((size_t)bb * P.T + t) * P.H + hp * P.p + dh) * P.W + wp * P.p + dw) * P.C + c;
+          P.eps[idx] = acc[e] + b;
+        }
+      }
+    }
+  }
+};
+
+// ---------------------------------------------------------------- attention problem description
+// One problem = one (batch row b, head, group g).  Query i of the problem is token
+// g*q_gstride + i*q_istride of batch row b; key j likewise with the k_* strides.
+//   q  [B, heads, q_tokens, hd]     k [KB, heads, k_tokens, hd]
+//   vt [KB, heads, hd, k_tokens_pad]
+//   out[B, q_tokens, heads*hd]      (token-major, heads concatenated)
+// Keys of batch row b come from key batch kb = b < kv_split ? b : kv_split when
+// kv_shared_tail is set (guidance rows share one 'null' text), else kb = b.
+struct AttnParams {
+  const void* q; const void* k; const void* vt; void* out;
+  int B, heads, hd;
+  int groups, nq, nk;
+  int q_tokens, q_gstride, q_istride;
+  int k_tokens, k_tokens_pad, k_gstride, k_istride;
+  int kv_split, kv_shared_tail;
+  float scale_log2;   // softmax scale times log2(e)
+};
+
+// ---------------------------------------------------------------- launchers (defined in the .hip files)
+hipError_t launch_convert_f32(const float* in, void* out, size_t n, int to_bf16, hipStream_t s);
+hipError_t launch_transpose_convert(const float* in, void* out, int rows, int cols, int to_bf16, hipStream_t s);
+hipError_t launch_act_to_f32_rows(int bf16, const void* in, float* out, int rows, int D,
+                                  int in_rows_per_b, int out_rows_per_b, int out_row_off,
+                                  int in_b_split, int in_shared_tail, hipStream_t s);
+hipError_t launch_sinusoid(float t, int dim, float* out, hipStream_t s);
+hipError_t launch_gemv(int bf16, const float* in, int K, const void* Wt, const float* bias, float* out, int N,
+                       int in_silu, int out_silu, int layers, size_t w_layer_stride, size_t b_layer_stride,
+                       size_t out_layer_stride, hipStream_t s);
+hipError_t launch_patch_embed(const float* latent, int R, int B, const float* Wp, const float* bp,
+                              const float* pos_sp, const float* pos_t, float* x, int T, int H, int W, int C,
+                              int p, int D, int rows_per_b, int row_off, hipStream_t s);
+hipError_t launch_ln_modulate(int bf16, const float* x, const float* shift, const float* scale, void* out,
+                              int rows, int D, float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off,
+                              hipStream_t s);
+hipError_t launch_cfg_ddim(float* x, const float* eps_c, const float* eps_u, float* eps_out, size_t n,
+                           float gscale, float c0, float c1, float c2, float c3, hipStream_t s);
+hipError_t launch_gemm(int bf16, int mode, const void* A, const void* Wt, int M, int N, int K,
+                       const EpiParams& ep, hipStream_t s);
+hipError_t launch_attention(int bf16, const AttnParams& p, int impl, hipStream_t s);
+
+}  // namespace fc

@@ -1,0 +1,312 @@
+// HBM-bound kernels of the denoising step: dtype conversion, timestep sinusoid,
+// batched GEMV (timestep MLP and adaLN modulation vectors), patch embedding,
+// LayerNorm + modulate, and the fused guidance + DDIM latent update.
+#include "common.h"
+
+namespace fc {
+
+// ---------------------------------------------------------------- conversions
+template <typename T>
+__global__ void k_convert(const float* __restrict__ in, T* __restrict__ out, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) out[i] = from_f32<T>(in[i]);
+}
+
+hipError_t launch_convert_f32(const float* in, void* out, size_t n, int to_bf16, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  int blocks = (int)((n + 255) / 256);
+  if (blocks > 65536) blocks = 65536;
+  if (to_bf16) k_convert<bf16_t><<<blocks, 256, 0, s>>>(in, (bf16_t*)out, n);
+  else k_convert<float><<<blocks, 256, 0, s>>>(in, (float*)out, n);
+  return hipGetLastError();
+}
+
+// in [rows, cols] fp32 row-major -> out [cols, rows] (T): linear weights are kept
+// [out, in] on the device so that both GEMM operands are contiguous along K.
+template <typename T>
+__global__ void k_transpose_convert(const float* __restrict__ in, T* __restrict__ out, int rows, int cols) {
+  __shared__ float tile[32][33];
+  int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+  int tx = threadIdx.x, ty = threadIdx.y;   // 32 x 8
+  for (int j = ty; j < 32; j += 8) {
+    int r = r0 + j, c = c0 + tx;
+    tile[j][tx] = (r < rows && c < cols) ? in[(size_t)r * cols + c] : 0.0f;
+  }
+  __syncthreads();
+  for (int j = ty; j < 32; j += 8) {
+    int c = c0 + j, r = r0 + tx;
+    if (c < cols && r < rows) out[(size_t)c * rows + r] = from_f32<T>(tile[tx][j]);
+  }
+}
+
+hipError_t launch_transpose_convert(const float* in, void* out, int rows, int cols, int to_bf16, hipStream_t s) {
+  dim3 grid(ceil_div(cols, 32), ceil_div(rows, 32)), block(32, 8);
+  if (to_bf16) k_transpose_convert<bf16_t><<<grid, block, 0, s>>>(in, (bf16_t*)out, rows, cols);
+  else k_transpose_convert<float><<<grid, block, 0, s>>>(in, (float*)out, rows, cols);
+  return hipGetLastError();
+}
+
+// Copy activation rows into the fp32 residual stream (text rows of the full-3D
+// sequence).  Output row (b, out_row_off + r) <- input row (src_b(b), r).
+template <typename T>
+__global__ void k_act_to_f32_rows(const T* __restrict__ in, float* __restrict__ out, int D, int in_rows_per_b,
+                                  int out_rows_per_b, int out_row_off, int in_b_split, int in_shared_tail) {
+  int row = blockIdx.x;                 // over B * in_rows_per_b
+  int b = row / in_rows_per_b, r = row % in_rows_per_b;
+  int sb = (in_shared_tail && b >= in_b_split) ? in_b_split : b;
+  const T* src = in + ((size_t)sb * in_rows_per_b + r) * D;
+  float* dst = out + ((size_t)b * out_rows_per_b + out_row_off + r) * D;
+  for (int c = threadIdx.x; c < D; c += blockDim.x) dst[c] = to_f32(src[c]);
+}
+
+hipError_t launch_act_to_f32_rows(int bf16, const void* in, float* out, int rows, int D, int in_rows_per_b,
+                                  int out_rows_per_b, int out_row_off, int in_b_split, int in_shared_tail,
+                                  hipStream_t s) {
+  if (rows == 0) return hipSuccess;
+  if (bf16) k_act_to_f32_rows<bf16_t><<<rows, 256, 0, s>>>((const bf16_t*)in, out, D, in_rows_per_b,
+                                                           out_rows_per_b, out_row_off, in_b_split, in_shared_tail);
+  else k_act_to_f32_rows<float><<<rows, 256, 0, s>>>((const float*)in, out, D, in_rows_per_b, out_rows_per_b,
+                                                      out_row_off, in_b_split, in_shared_tail);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- timestep sinusoid
+// out = [cos(t f_0..f_{h-1}) | sin(t f_0..f_{h-1})], f_i = 10000^(-i/h), h = dim/2.
+// Arguments reach ~1e3 rad; the angle is formed in double so that fp32 range
+// reduction does not cost accuracy.
+__global__ void k_sinusoid(float t, int dim, float* __restrict__ out) {
+  int half = dim / 2;
+  for (int i = threadIdx.x; i < half; i += blockDim.x) {
+    double f = exp(-log(10000.0) * (double)i / (double)half);
+    double a = (double)t * f;
+    out[i] = (float)cos(a);
+    out[half + i] = (float)sin(a);
+  }
+}
+
+hipError_t launch_sinusoid(float t, int dim, float* out, hipStream_t s) {
+  k_sinusoid<<<1, 128, 0, s>>>(t, dim, out);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- GEMV
+// out[l][n] = f_out( sum_k f_in(in[k]) * Wt[l][n][k] + bias[l][n] ), one wave per
+// output element, lanes striding K with 16-byte loads.  The input vector is
+// shared by all layers l (the adaLN layers of every block read the same SiLU(c)).
+template <typename T>
+__global__ void k_gemv(const float* __restrict__ in, int K, const T* __restrict__ Wt, const float* __restrict__ bias,
+                       float* __restrict__ out, int N, int in_silu, int out_silu, size_t w_layer_stride,
+                       size_t b_layer_stride, size_t out_layer_stride) {
+  extern __shared__ float s_in[];
+  for (int k = threadIdx.x; k < K; k += blockDim.x) {
+    float v = in[k];
+    s_in[k] = in_silu ? silu_f(v) : v;
+  }
+  __syncthreads();
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = blockIdx.x * (blockDim.x >> 6) + wave;
+  const int l = blockIdx.y;
+  if (n >= N) return;
+  const T* w = Wt + l * w_layer_stride + (size_t)n * K;
+  float acc = 0.0f;
+  constexpr int V = 16 / sizeof(T);
+  if (K % V == 0) {
+    for (int k = lane * V; k < K; k += 64 * V) {
+      if constexpr (sizeof(T) == 2) {
+        bf16x8 wv = *(const bf16x8*)(w + k);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc += s_in[k + e] * (float)wv[e];
+      } else {
+        f32x4 wv = *(const f32x4*)(w + k);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc += s_in[k + e] * wv[e];
+      }
+    }
+  } else {
+    for (int k = lane; k < K; k += 64) acc += s_in[k] * to_f32(w[k]);
+  }
+  acc = wave_sum(acc);
+  if (lane == 0) {
+    float v = acc + bias[l * b_layer_stride + n];
+    out[l * out_layer_stride + n] = out_silu ? silu_f(v) : v;
+  }
+}
+
+hipError_t launch_gemv(int bf16, const float* in, int K, const void* Wt, const float* bias, float* out, int N,
+                       int in_silu, int out_silu, int layers, size_t w_layer_stride, size_t b_layer_stride,
+                       size_t out_layer_stride, hipStream_t s) {
+  if (N == 0 || layers == 0) return hipSuccess;
+  dim3 grid(ceil_div(N, 4), layers);
+  size_t sh = (size_t)K * sizeof(float);
+  if (bf16) k_gemv<bf16_t><<<grid, 256, sh, s>>>(in, K, (const bf16_t*)Wt, bias, out, N, in_silu, out_silu,
+                                                 w_layer_stride, b_layer_stride, out_layer_stride);
+  else k_gemv<float><<<grid, 256, sh, s>>>(in, K, (const float*)Wt, bias, out, N, in_silu, out_silu,
+                                           w_layer_stride, b_layer_stride, out_layer_stride);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- patch embedding
+// x[b, row_off + n, :] = patch(latent[b % R], n) . Wp + bp + pos_sp[s] + pos_t[t]
+// with n = t*S + s, patch feature order (dh, dw, c).  K = p*p*C is tiny, so the
+// kernel is bound by the write of x: a block takes TOK tokens so that Wp is read
+// from L2 once per TOK rows, and each thread owns 4 consecutive columns.
+constexpr int PE_TOK = 16;
+__global__ void k_patch_embed(const float* __restrict__ latent, int R, const float* __restrict__ Wp,
+                              const float* __restrict__ bp, const float* __restrict__ pos_sp,
+                              const float* __restrict__ pos_t, float* __restrict__ x, int T, int H, int W, int C,
+                              int p, int D, int rows_per_b, int row_off) {
+  extern __shared__ float s_patch[];   // [PE_TOK][pd]
+  const int pd = p * p * C;
+  const int gw = W / p, S = (H / p) * gw, N = T * S;
+  const int b = blockIdx.y;
+  const int n0 = blockIdx.x * PE_TOK;
+  const float* lat = latent + (size_t)(b % R) * T * H * W * C;
+  for (int i = threadIdx.x; i < PE_TOK * pd; i += blockDim.x) {
+    int tk = i / pd, f = i % pd;
+    int n = n0 + tk;
+    float v = 0.0f;
+    if (n < N) {
+      int t = n / S, s = n % S, hp = s / gw, wp = s % gw;
+      int dh = f / (p * C), dw = (f / C) % p, c = f % C;
+      v = lat[(((size_t)t * H + hp * p + dh) * W + wp * p + dw) * C + c];
+    }
+    s_patch[i] = v;
+  }
+  __syncthreads();
+  for (int c0 = threadIdx.x * 4; c0 < D; c0 += blockDim.x * 4) {
+    f32x4 acc[PE_TOK];
+#pragma unroll
+    for (int tk = 0; tk < PE_TOK; ++tk) acc[tk] = f32x4{0, 0, 0, 0};
+    for (int f = 0; f < pd; ++f) {
+      f32x4 w = *(const f32x4*)(Wp + (size_t)f * D + c0);
+#pragma unroll
+      for (int tk = 0; tk < PE_TOK; ++tk) acc[tk] += s_patch[tk * pd + f] * w;
+    }
+    f32x4 bias = *(const f32x4*)(bp + c0);
+#pragma unroll
+    for (int tk = 0; tk < PE_TOK; ++tk) {
+      int n = n0 + tk;
+      if (n < N) {
+        int t = n / S, s = n % S;
+        f32x4 ps = *(const f32x4*)(pos_sp + (size_t)s * D + c0);
+        f32x4 pt = *(const f32x4*)(pos_t + (size_t)t * D + c0);
+        *(f32x4*)(x + ((size_t)b * rows_per_b + row_off + n) * D + c0) = acc[tk] + bias + (ps + pt);
+      }
+    }
+  }
+}
+
+hipError_t launch_patch_embed(const float* latent, int R, int B, const float* Wp, const float* bp,
+                              const float* pos_sp, const float* pos_t, float* x, int T, int H, int W, int C,
+                              int p, int D, int rows_per_b, int row_off, hipStream_t s) {
+  int N = T * (H / p) * (W / p);
+  dim3 grid(ceil_div(N, PE_TOK), B);
+  size_t sh = (size_t)PE_TOK * p * p * C * sizeof(float);
+  k_patch_embed<<<grid, 256, sh, s>>>(latent, R, Wp, bp, pos_sp, pos_t, x, T, H, W, C, p, D, rows_per_b, row_off);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- LayerNorm + modulate
+// One wave per row: the row is staged in LDS, mean and centred variance are wave
+// reductions (two passes over LDS, never over HBM), then
+// out = (x - mean) * rsqrt(var + eps) * (1 + scale) + shift.
+// Output row r (0..rows) reads input row (r / out_rows_per_b) * in_rows_per_b +
+// in_row_off + r % out_rows_per_b, which lets the final layer skip text rows.
+template <typename T>
+__global__ void k_ln_modulate(const float* __restrict__ x, const float* __restrict__ shift,
+                              const float* __restrict__ scale, T* __restrict__ out, int rows, int D, float eps,
+                              int in_rows_per_b, int out_rows_per_b, int in_row_off) {
+  extern __shared__ float s_row[];      // [waves][D]
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int r = blockIdx.x * (blockDim.x >> 6) + wave;
+  if (r >= rows) return;
+  const size_t in_r = (size_t)(r / out_rows_per_b) * in_rows_per_b + in_row_off + (r % out_rows_per_b);
+  const float* xr = x + in_r * D;
+  float* sr = s_row + (size_t)wave * D;
+  float sum = 0.0f;
+  for (int c = lane * 4; c < D; c += 256) {
+    f32x4 v = *(const f32x4*)(xr + c);
+    *(f32x4*)(sr + c) = v;
+    sum += (v[0] + v[1]) + (v[2] + v[3]);
+  }
+  const float mean = wave_sum(sum) / (float)D;
+  float sq = 0.0f;
+  for (int c = lane * 4; c < D; c += 256) {
+    f32x4 v = *(const f32x4*)(sr + c) - mean;
+    sq += (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
+  }
+  const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)D + eps);
+  T* o = out + (size_t)r * D;
+  for (int c = lane * 4; c < D; c += 256) {
+    f32x4 v = (*(const f32x4*)(sr + c) - mean) * rstd;
+    if (scale) {
+      f32x4 sc = *(const f32x4*)(scale + c), sh = *(const f32x4*)(shift + c);
+      v = v * (1.0f + sc) + sh;
+    }
+    if constexpr (sizeof(T) == 2) {
+      bf16x4 ov;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)v[e];
+      *(bf16x4*)(o + c) = ov;
+    } else {
+      *(f32x4*)(o + c) = v;
+    }
+  }
+}
+
+hipError_t launch_ln_modulate(int bf16, const float* x, const float* shift, const float* scale, void* out,
+                              int rows, int D, float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off,
+                              hipStream_t s) {
+  if (rows == 0) return hipSuccess;
+  const int waves = 4;
+  size_t sh = (size_t)waves * D * sizeof(float);
+  dim3 grid(ceil_div(rows, waves));
+  if (bf16) k_ln_modulate<bf16_t><<<grid, waves * 64, sh, s>>>(x, shift, scale, (bf16_t*)out, rows, D, eps,
+                                                               in_rows_per_b, out_rows_per_b, in_row_off);
+  else k_ln_modulate<float><<<grid, waves * 64, sh, s>>>(x, shift, scale, (float*)out, rows, D, eps,
+                                                         in_rows_per_b, out_rows_per_b, in_row_off);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- guidance + DDIM update
+// eps = eps_u + s (eps_c - eps_u);  x0 = (x - c1 eps) / c0;  x <- c2 x0 + c3 eps.
+// 16 algorithmic bytes per element with guidance (3 reads + 1 write).
+template <bool VEC>
+__global__ void k_cfg_ddim(float* __restrict__ x, const float* __restrict__ eps_c, const float* __restrict__ eps_u,
+                           float* __restrict__ eps_out, size_t n, float gs, float c0, float c1, float c2, float c3) {
+  size_t i = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (VEC && i + 3 < n) {
+    f32x4 e = *(const f32x4*)(eps_c + i);
+    if (eps_u) {
+      f32x4 u = *(const f32x4*)(eps_u + i);
+      e = u + gs * (e - u);
+    }
+    f32x4 xv = *(const f32x4*)(x + i);
+    f32x4 x0 = (xv - c1 * e) / c0;
+    *(f32x4*)(x + i) = c2 * x0 + c3 * e;
+    if (eps_out) *(f32x4*)(eps_out + i) = e;
+  } else {
+    for (size_t end = i + 4 < n ? i + 4 : n; i < end; ++i) {
+      float e = eps_c[i];
+      if (eps_u) e = eps_u[i] + gs * (e - eps_u[i]);
+      float x0 = (x[i] - c1 * e) / c0;
+      x[i] = c2 * x0 + c3 * e;
+      if (eps_out) eps_out[i] = e;
+    }
+  }
+}
+
+hipError_t launch_cfg_ddim(float* x, const float* eps_c, const float* eps_u, float* eps_out, size_t n,
+                           float gscale, float c0, float c1, float c2, float c3, hipStream_t s) {
+  if (n == 0) return hipSuccess;
+  size_t threads = (n + 3) / 4;
+  unsigned blocks = (unsigned)((threads + 255) / 256);
+  // 16-byte vector access needs every pointer aligned; otherwise each thread walks its 4 elements
+  uintptr_t al = (uintptr_t)x | (uintptr_t)eps_c | (uintptr_t)eps_u | (uintptr_t)eps_out;
+  if ((al & 15) == 0) k_cfg_ddim<true><<<blocks, 256, 0, s>>>(x, eps_c, eps_u, eps_out, n, gscale, c0, c1, c2, c3);
+  else k_cfg_ddim<false><<<blocks, 256, 0, s>>>(x, eps_c, eps_u, eps_out, n, gscale, c0, c1, c2, c3);
+  return hipGetLastError();
+}
+
+}  // namespace fc

@@ -1,0 +1,667 @@
+// C ABI and host orchestration of the denoising step / cache-hit resume loop.
+// The host builds the launch sequence of one step; nothing here synchronises the
+// stream or reads device memory back, so a resume call enqueues all N-k steps.
+#include "../../include/flexdenoise.h"
+#include "common.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+using namespace fc;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const std::string& msg) {
+  g_err = msg;
+  return code;
+}
+int fail_hip(hipError_t e, const char* where) {
+  g_err = std::string(where) + ": " + hipGetErrorString(e);
+  return FC_ERR_DEVICE;
+}
+#define HIP_TRY(expr)                                         \
+  do {                                                        \
+    hipError_t _e = (expr);                                   \
+    if (_e != hipSuccess) return fail_hip(_e, #expr);         \
+  } while (0)
+
+struct Linear {           // weights [out, in] in the activation dtype, bias fp32
+  void* wt = nullptr;
+  float* b = nullptr;
+  int in = 0, out = 0;
+};
+
+struct Block {
+  Linear qkv[2], proj[2];          // [0] spatial / full-3D, [1] temporal
+  Linear xq, xkv, xproj;           // cross-attention (factorized mode)
+  Linear fc1, fc2;
+};
+
+}  // namespace
+
+struct fc_model {
+  fc_model_config cfg;
+  int device = 0;
+  bool has_weights = false;
+  bool bf16 = false;
+  int S = 0, N = 0, Ns = 0, pd = 0, hd = 0, nmod = 0;
+  size_t esz = 4;                  // bytes per activation / weight element
+
+  unsigned char* wbuf = nullptr;   // one device allocation for all parameters and tables
+  size_t wbytes = 0;
+  Linear t1, t2, y, fmod, fout;
+  float* p_w = nullptr;            // patch embedding stays fp32 [pd, D] (K is tiny)
+  float* p_b = nullptr;
+  void* mod_w = nullptr;           // [depth][nmod*D, D]
+  float* mod_b = nullptr;          // [depth][nmod*D]
+  float* pos_sp = nullptr;         // [S, D]
+  float* pos_t = nullptr;          // [T, D]
+  std::vector<Block> blocks;
+};
+
+namespace {
+
+// ---------------------------------------------------------------- schedule (host, double)
+int schedule_check(const fc_schedule* s) {
+  if (!s) return fail(FC_ERR_NULL, "schedule is NULL");
+  if (s->eta != 0.0f) return fail(FC_ERR_UNSUPPORTED, "only the deterministic sampler (eta = 0) is implemented");
+  if (s->train_steps < 1 || s->num_steps < 1 || s->num_steps > s->train_steps)
+    return fail(FC_ERR_RANGE, "need 1 <= num_steps <= train_steps");
+  return FC_OK;
+}
+
+double abar_at(const fc_schedule* s, int t) {
+  double prod = 1.0;
+  const double denom = s->train_steps > 1 ? (double)(s->train_steps - 1) : 1.0;
+  for (int i = 0; i <= t; ++i) {
+    double beta = (double)s->beta_start + ((double)s->beta_end - (double)s->beta_start) * (double)i / denom;
+    prod *= 1.0 - beta;
+  }
+  return prod;
+}
+
+int step_coefficients(const fc_schedule* s, int step, float* out4, int* t_out) {
+  int rc = schedule_check(s);
+  if (rc != FC_OK) return rc;
+  const int N = s->num_steps;
+  if (step < 1 || step > N) return fail(FC_ERR_RANGE, "step must be in 1..num_steps");
+  const int stride = s->train_steps / N;
+  const int t = (N - step) * stride;
+  const double a_t = abar_at(s, t);
+  const double a_p = step == N ? 1.0 : abar_at(s, (N - step - 1) * stride);
+  out4[0] = (float)std::sqrt(a_t);
+  out4[1] = (float)std::sqrt(1.0 - a_t);
+  out4[2] = (float)std::sqrt(a_p);
+  out4[3] = (float)std::sqrt(1.0 - a_p);
+  if (t_out) *t_out = t;
+  return FC_OK;
+}
+
+// ---------------------------------------------------------------- weight blob walking
+struct BlobItem { size_t off; int rows, cols; };   // matrices [rows, cols]; vectors rows = 1
+
+size_t weight_count(const fc_model_config& c) {
+  const size_t D = c.hidden, M = c.mlp_dim, te = c.t_embed_dim, dt = c.text_dim;
+  const size_t pd = (size_t)c.patch * c.patch * c.channels;
+  size_t n = te * D + D + D * D + D + dt * D + D + pd * D + D;
+  size_t per;
+  if (c.attn_mode == FC_ATTN_FACTORIZED_CROSS)
+    per = D * 9 * D + 9 * D + 2 * (D * 3 * D + 3 * D + D * D + D) + (D * D + D) + (D * 2 * D + 2 * D) + (D * D + D);
+  else
+    per = D * 6 * D + 6 * D + (D * 3 * D + 3 * D + D * D + D);
+  per += D * M + M + M * D + D;
+  n += per * c.depth;
+  n += D * 2 * D + 2 * D + D * pd + pd;
+  return n;
+}
+
+struct Carver {          // bump allocator over a byte range, 256-byte aligned pieces
+  unsigned char* base;
+  size_t off = 0;
+  explicit Carver(unsigned char* b) : base(b) {}
+  void* take(size_t bytes) {
+    void* p = base ? base + off : nullptr;
+    off += round_up(bytes, 256);
+    return p;
+  }
+};
+
+// Lays out (base != NULL) or sizes (base == NULL) the parameter buffer.
+size_t layout_weights(fc_model* m, unsigned char* base) {
+  const fc_model_config& c = m->cfg;
+  const size_t D = c.hidden, M = c.mlp_dim, es = m->esz;
+  Carver cv(base);
+  auto lin = [&](Linear& L, int in, int out) {
+    L.in = in; L.out = out;
+    L.wt = cv.take((size_t)in * out * es);
+    L.b = (float*)cv.take((size_t)out * 4);
+  };
+  lin(m->t1, c.t_embed_dim, D);
+  lin(m->t2, D, D);
+  lin(m->y, c.text_dim, D);
+  m->p_w = (float*)cv.take((size_t)m->pd * D * 4);
+  m->p_b = (float*)cv.take(D * 4);
+  m->mod_w = cv.take((size_t)c.depth * m->nmod * D * D * es);
+  m->mod_b = (float*)cv.take((size_t)c.depth * m->nmod * D * 4);
+  m->blocks.resize(c.depth);
+  for (int l = 0; l < c.depth; ++l) {
+    Block& b = m->blocks[l];
+    lin(b.qkv[0], D, 3 * D);
+    lin(b.proj[0], D, D);
+    if (c.attn_mode == FC_ATTN_FACTORIZED_CROSS) {
+      lin(b.qkv[1], D, 3 * D);
+      lin(b.proj[1], D, D);
+      lin(b.xq, D, D);
+      lin(b.xkv, D, 2 * D);
+      lin(b.xproj, D, D);
+    }
+    lin(b.fc1, D, M);
+    lin(b.fc2, M, D);
+  }
+  lin(m->fmod, D, 2 * D);
+  lin(m->fout, D, m->pd);
+  m->pos_sp = (float*)cv.take((size_t)m->S * D * 4);
+  m->pos_t = (float*)cv.take((size_t)c.frames * D * 4);
+  return cv.off;
+}
+
+void sincos_1d(double pos, int dim, float* out) {   // [sin(pos w_i) | cos(pos w_i)], w_i = 10000^(-i/(dim/2))
+  const int half = dim / 2;
+  for (int i = 0; i < half; ++i) {
+    double w = std::pow(10000.0, -(double)i / (double)half);
+    out[i] = (float)std::sin(pos * w);
+    out[half + i] = (float)std::cos(pos * w);
+  }
+}
+
+// ---------------------------------------------------------------- workspace
+struct Workspace {
+  float *e, *h1, *c, *mod, *fmod;          // timestep path, fp32
+  void *txt, *y;                           // text in act dtype, projected text
+  void *xk, *xvt;                          // cross-attention K / V^T per block (factorized)
+  float* x;                                // residual stream fp32 [B, Ns, D]
+  void *u, *q, *k, *vt, *hid;              // activations
+  float* eps;                              // [B, T, H, W, C]
+  size_t bytes;
+  int B, NT, Nsp, Lp;
+};
+
+Workspace carve(const fc_model* m, int R, int use_cfg, unsigned char* base) {
+  const fc_model_config& c = m->cfg;
+  const size_t D = c.hidden, es = m->esz;
+  Workspace w{};
+  w.B = R * (use_cfg ? 2 : 1);
+  w.NT = R + (use_cfg ? 1 : 0);                 // distinct texts: R prompts (+ the shared null)
+  w.Nsp = (int)round_up(m->Ns, 64);
+  w.Lp = (int)round_up(c.text_len, 64);
+  const size_t rows = (size_t)w.B * m->Ns;
+  Carver cv(base);
+  w.e = (float*)cv.take((size_t)c.t_embed_dim * 4);
+  w.h1 = (float*)cv.take(D * 4);
+  w.c = (float*)cv.take(D * 4);
+  w.mod = (float*)cv.take((size_t)c.depth * m->nmod * D * 4);
+  w.fmod = (float*)cv.take(2 * D * 4);
+  w.txt = cv.take((size_t)w.NT * c.text_len * c.text_dim * es);
+  w.y = cv.take((size_t)w.NT * c.text_len * D * es);
+  if (c.attn_mode == FC_ATTN_FACTORIZED_CROSS) {
+    w.xk = cv.take((size_t)c.depth * w.NT * c.text_len * D * es);
+    w.xvt = cv.take((size_t)c.depth * w.NT * w.Lp * D * es);
+  }
+  w.x = (float*)cv.take(rows * D * 4);
+  w.u = cv.take(rows * D * es);
+  w.q = cv.take(rows * D * es);
+  w.k = cv.take(rows * D * es);
+  w.vt = cv.take((size_t)w.B * D * w.Nsp * es);
+  w.hid = cv.take(rows * c.mlp_dim * es);
+  w.eps = (float*)cv.take((size_t)w.B * c.frames * c.height * c.width * c.channels * 4);
+  w.bytes = cv.off;
+  return w;
+}
+
+// ---------------------------------------------------------------- step building blocks
+struct Ctx {
+  fc_model* m;
+  Workspace w;
+  int R, use_cfg;
+  hipStream_t s;
+};
+
+int linear(const Ctx& c, int mode, const void* A, const Linear& L, int M, EpiParams ep) {
+  ep.bias = L.b;
+  HIP_TRY(launch_gemm(c.m->bf16, mode, A, L.wt, M, L.out, L.in, ep, c.s));
+  return FC_OK;
+}
+
+EpiParams heads_epi(const Ctx& c, void* q, void* k, void* vt, int which0, int tokens, int tokens_pad) {
+  EpiParams ep;
+  ep.q = q; ep.k = k; ep.vt = vt;
+  ep.which0 = which0;
+  ep.D = c.m->cfg.hidden; ep.heads = c.m->cfg.heads; ep.hd = c.m->hd;
+  ep.tokens = tokens; ep.tokens_pad = tokens_pad;
+  return ep;
+}
+
+// Timestep-invariant work: text to the activation dtype, text projection, and (factorized
+// mode) the cross-attention keys / values of every block.
+int prepare(const Ctx& c, const float* cond, const float* null_cond) {
+  const fc_model* m = c.m;
+  const fc_model_config& cf = m->cfg;
+  const Workspace& w = c.w;
+  const size_t per_text = (size_t)cf.text_len * cf.text_dim;
+  HIP_TRY(launch_convert_f32(cond, w.txt, per_text * c.R, m->bf16, c.s));
+  if (c.use_cfg)
+    HIP_TRY(launch_convert_f32(null_cond, (unsigned char*)w.txt + per_text * c.R * m->esz, per_text, m->bf16, c.s));
+  EpiParams ep;
+  ep.out = w.y; ep.ldo = cf.hidden;
+  int rc = linear(c, EPI_STORE, w.txt, m->y, w.NT * cf.text_len, ep);
+  if (rc != FC_OK) return rc;
+  if (cf.attn_mode == FC_ATTN_FACTORIZED_CROSS) {
+    for (int l = 0; l < cf.depth; ++l) {
+      void* xk = (unsigned char*)w.xk + (size_t)l * w.NT * cf.text_len * cf.hidden * m->esz;
+      void* xvt = (unsigned char*)w.xvt + (size_t)l * w.NT * w.Lp * cf.hidden * m->esz;
+      rc = linear(c, EPI_HEADS, w.y, m->blocks[l].xkv, w.NT * cf.text_len,
+                  heads_epi(c, nullptr, xk, xvt, 1, cf.text_len, w.Lp));
+      if (rc != FC_OK) return rc;
+    }
+  }
+  return FC_OK;
+}
+
+int ln_mod(const Ctx& c, const float* shift, const float* scale) {
+  const fc_model* m = c.m;
+  HIP_TRY(launch_ln_modulate(m->bf16, c.w.x, shift, scale, c.w.u, c.w.B * m->Ns, m->cfg.hidden, m->cfg.ln_eps,
+                             m->Ns, m->Ns, 0, c.s));
+  return FC_OK;
+}
+
+// Self-attention branch: x += gate * proj(attn(qkv(u))).  mode 0 spatial, 1 temporal, 2 all tokens.
+int self_attention_branch(const Ctx& c, const Linear& qkv, const Linear& proj, const float* gate, int mode) {
+  const fc_model* m = c.m;
+  const fc_model_config& cf = m->cfg;
+  const Workspace& w = c.w;
+  const int rows = w.B * m->Ns;
+  int rc = linear(c, EPI_HEADS, w.u, qkv, rows, heads_epi(c, w.q, w.k, w.vt, 0, m->Ns, w.Nsp));
+  if (rc != FC_OK) return rc;
+  AttnParams ap{};
+  ap.q = w.q; ap.k = w.k; ap.vt = w.vt; ap.out = w.u;
+  ap.B = w.B; ap.heads = cf.heads; ap.hd = m->hd;
+  ap.q_tokens = ap.k_tokens = m->Ns; ap.k_tokens_pad = w.Nsp;
+  if (mode == 0) { ap.groups = cf.frames; ap.nq = ap.nk = m->S; ap.q_gstride = ap.k_gstride = m->S; ap.q_istride = ap.k_istride = 1; }
+  else if (mode == 1) { ap.groups = m->S; ap.nq = ap.nk = cf.frames; ap.q_gstride = ap.k_gstride = 1; ap.q_istride = ap.k_istride = m->S; }
+  else { ap.groups = 1; ap.nq = ap.nk = m->Ns; ap.q_gstride = ap.k_gstride = 0; ap.q_istride = ap.k_istride = 1; }
+  ap.kv_split = 0; ap.kv_shared_tail = 0;
+  ap.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)m->hd));
+  HIP_TRY(launch_attention(m->bf16, ap, 0, c.s));
+  EpiParams ep;
+  ep.x = w.x; ep.ldo = cf.hidden; ep.gate = gate;
+  return linear(c, EPI_RESID, w.u, proj, rows, ep);
+}
+
+int cross_attention_branch(const Ctx& c, const Block& b, int layer) {
+  const fc_model* m = c.m;
+  const fc_model_config& cf = m->cfg;
+  const Workspace& w = c.w;
+  const int rows = w.B * m->Ns;
+  int rc = ln_mod(c, nullptr, nullptr);
+  if (rc != FC_OK) return rc;
+  rc = linear(c, EPI_HEADS, w.u, b.xq, rows, heads_epi(c, w.q, nullptr, nullptr, 0, m->Ns, w.Nsp));
+  if (rc != FC_OK) return rc;
+  AttnParams ap{};
+  ap.q = w.q;
+  ap.k = (unsigned char*)w.xk + (size_t)layer * w.NT * cf.text_len * cf.hidden * m->esz;
+  ap.vt = (unsigned char*)w.xvt + (size_t)layer * w.NT * w.Lp * cf.hidden * m->esz;
+  ap.out = w.u;
+  ap.B = w.B; ap.heads = cf.heads; ap.hd = m->hd;
+  ap.groups = 1; ap.nq = m->Ns; ap.nk = cf.text_len;
+  ap.q_tokens = m->Ns; ap.q_gstride = 0; ap.q_istride = 1;
+  ap.k_tokens = cf.text_len; ap.k_tokens_pad = w.Lp; ap.k_gstride = 0; ap.k_istride = 1;
+  ap.kv_split = c.R; ap.kv_shared_tail = c.use_cfg;      // guidance rows all read the null text
+  ap.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)m->hd));
+  HIP_TRY(launch_attention(m->bf16, ap, 0, c.s));
+  EpiParams ep;
+  ep.x = w.x; ep.ldo = cf.hidden; ep.gate = nullptr;
+  return linear(c, EPI_RESID, w.u, b.xproj, rows, ep);
+}
+
+int mlp_branch(const Ctx& c, const Block& b, const float* mod) {
+  const fc_model* m = c.m;
+  const int D = m->cfg.hidden, rows = c.w.B * m->Ns;
+  int rc = ln_mod(c, mod, mod + D);
+  if (rc != FC_OK) return rc;
+  EpiParams e1;
+  e1.out = c.w.hid; e1.ldo = m->cfg.mlp_dim;
+  rc = linear(c, EPI_GELU, c.w.u, b.fc1, rows, e1);
+  if (rc != FC_OK) return rc;
+  EpiParams e2;
+  e2.x = c.w.x; e2.ldo = D; e2.gate = mod + 2 * D;
+  return linear(c, EPI_RESID, c.w.hid, b.fc2, rows, e2);
+}
+
+// One forward pass of all B rows + guidance + DDIM update of the R latents.
+int run_step(const Ctx& c, float* latent, const fc_schedule* sched, int step, float* eps_out) {
+  fc_model* m = c.m;
+  const fc_model_config& cf = m->cfg;
+  const Workspace& w = c.w;
+  const int D = cf.hidden;
+  float coef[4];
+  int t = 0;
+  int rc = step_coefficients(sched, step, coef, &t);
+  if (rc != FC_OK) return rc;
+
+  // conditioning: sinusoid -> Linear -> SiLU -> Linear -> c; every adaLN layer reads SiLU(c)
+  HIP_TRY(launch_sinusoid((float)t, cf.t_embed_dim, w.e, c.s));
+  HIP_TRY(launch_gemv(m->bf16, w.e, cf.t_embed_dim, m->t1.wt, m->t1.b, w.h1, D, 0, 1, 1, 0, 0, 0, c.s));
+  HIP_TRY(launch_gemv(m->bf16, w.h1, D, m->t2.wt, m->t2.b, w.c, D, 0, 0, 1, 0, 0, 0, c.s));
+  const int nm = m->nmod * D;
+  HIP_TRY(launch_gemv(m->bf16, w.c, D, m->mod_w, m->mod_b, w.mod, nm, 1, 0, cf.depth, (size_t)nm * D, nm, nm, c.s));
+  HIP_TRY(launch_gemv(m->bf16, w.c, D, m->fmod.wt, m->fmod.b, w.fmod, 2 * D, 1, 0, 1, 0, 0, 0, c.s));
+
+  // tokens
+  const int text_rows = cf.attn_mode == FC_ATTN_FULL3D_CONCAT ? cf.text_len : 0;
+  HIP_TRY(launch_patch_embed(latent, c.R, w.B, m->p_w, m->p_b, m->pos_sp, m->pos_t, w.x, cf.frames, cf.height,
+                             cf.width, cf.channels, cf.patch, D, m->Ns, text_rows, c.s));
+  if (text_rows)
+    HIP_TRY(launch_act_to_f32_rows(m->bf16, w.y, w.x, w.B * cf.text_len, D, cf.text_len, m->Ns, 0, c.R, c.use_cfg,
+                                   c.s));
+
+  for (int l = 0; l < cf.depth; ++l) {
+    const Block& b = m->blocks[l];
+    const float* mod = w.mod + (size_t)l * nm;
+    if (cf.attn_mode == FC_ATTN_FACTORIZED_CROSS) {
+      for (int br = 0; br < 2; ++br) {
+        const float* mv = mod + (size_t)br * 3 * D;
+        if ((rc = ln_mod(c, mv, mv + D)) != FC_OK) return rc;
+        if ((rc = self_attention_branch(c, b.qkv[br], b.proj[br], mv + 2 * D, br)) != FC_OK) return rc;
+      }
+      if ((rc = cross_attention_branch(c, b, l)) != FC_OK) return rc;
+      if ((rc = mlp_branch(c, b, mod + 6 * D)) != FC_OK) return rc;
+    } else {
+      if ((rc = ln_mod(c, mod, mod + D)) != FC_OK) return rc;
+      if ((rc = self_attention_branch(c, b.qkv[0], b.proj[0], mod + 2 * D, 2)) != FC_OK) return rc;
+      if ((rc = mlp_branch(c, b, mod + 3 * D)) != FC_OK) return rc;
+    }
+  }
+
+  // head: LN + modulate on the video rows, Linear D -> p*p*C, scatter back to latent layout
+  HIP_TRY(launch_ln_modulate(m->bf16, w.x, w.fmod, w.fmod + D, w.u, w.B * m->N, D, cf.ln_eps, m->Ns, m->N,
+                             text_rows, c.s));
+  EpiParams ep;
+  ep.eps = w.eps; ep.T = cf.frames; ep.H = cf.height; ep.W = cf.width; ep.C = cf.channels; ep.p = cf.patch;
+  if ((rc = linear(c, EPI_UNPATCH, w.u, m->fout, w.B * m->N, ep)) != FC_OK) return rc;
+
+  const size_t n = (size_t)c.R * cf.frames * cf.height * cf.width * cf.channels;
+  HIP_TRY(launch_cfg_ddim(latent, w.eps, c.use_cfg ? w.eps + n : nullptr, eps_out, n, sched->guidance_scale,
+                          coef[0], coef[1], coef[2], coef[3], c.s));
+  return FC_OK;
+}
+
+int check_call(fc_model* m, const float* latent, const float* cond, const fc_schedule* sched, int R,
+               void* workspace, size_t workspace_bytes, int use_cfg, Ctx* ctx, void* stream) {
+  if (!m || !latent || !cond || !sched || !workspace) return fail(FC_ERR_NULL, "NULL argument");
+  if (!m->has_weights) return fail(FC_ERR_STATE, "fc_model_set_weights has not been called");
+  int rc = schedule_check(sched);
+  if (rc != FC_OK) return rc;
+  if (R < 1) return fail(FC_ERR_RANGE, "batch_requests must be >= 1");
+  if (((uintptr_t)workspace & 255) != 0) return fail(FC_ERR_WORKSPACE, "workspace must be 256-byte aligned");
+  Workspace w = carve(m, R, use_cfg, (unsigned char*)workspace);
+  if (w.bytes > workspace_bytes) return fail(FC_ERR_WORKSPACE, "workspace smaller than fc_workspace_bytes()");
+  if ((long long)w.B * m->Ns > (long long)INT32_MAX / 4) return fail(FC_ERR_RANGE, "batch too large");
+  ctx->m = m; ctx->w = w; ctx->R = R; ctx->use_cfg = use_cfg; ctx->s = (hipStream_t)stream;
+  return FC_OK;
+}
+
+}  // namespace
+
+// ================================================================ C ABI
+extern "C" {
+
+int fc_model_create(const fc_model_config* cfg, fc_model** out) {
+  if (!cfg || !out) return fail(FC_ERR_NULL, "NULL argument");
+  *out = nullptr;
+  const fc_model_config& c = *cfg;
+  if (c.frames < 1 || c.height < 1 || c.width < 1 || c.channels < 1 || c.patch < 1 || c.hidden < 1 ||
+      c.heads < 1 || c.mlp_dim < 1 || c.depth < 0 || c.text_len < 1 || c.text_dim < 1 || c.t_embed_dim < 2)
+    return fail(FC_ERR_SHAPE, "non-positive dimension");
+  if (c.height % c.patch || c.width % c.patch) return fail(FC_ERR_SHAPE, "height/width not divisible by patch");
+  if (c.hidden % c.heads) return fail(FC_ERR_SHAPE, "hidden not divisible by heads");
+  if (c.hidden % 4 || c.t_embed_dim % 2) return fail(FC_ERR_SHAPE, "hidden must be a multiple of 4, t_embed_dim even");
+  if (c.attn_mode != FC_ATTN_FACTORIZED_CROSS && c.attn_mode != FC_ATTN_FULL3D_CONCAT)
+    return fail(FC_ERR_SHAPE, "unknown attn_mode");
+  if (c.dtype != FC_F32 && c.dtype != FC_BF16) return fail(FC_ERR_SHAPE, "unknown dtype");
+  const int hd = c.hidden / c.heads;
+  const int ok_hd[] = {8, 16, 32, 64, 72, 96, 128};
+  bool hd_ok = false;
+  for (int v : ok_hd) hd_ok |= (v == hd);
+  if (!hd_ok) return fail(FC_ERR_SHAPE, "head dim must be one of 8,16,32,64,72,96,128");
+  if (!(c.ln_eps >= 0.0f)) return fail(FC_ERR_SHAPE, "ln_eps must be >= 0");
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  fc_model* m = new fc_model();
+  m->cfg = c;
+  m->device = dev;
+  m->bf16 = c.dtype == FC_BF16;
+  m->esz = m->bf16 ? 2 : 4;
+  m->S = (c.height / c.patch) * (c.width / c.patch);
+  m->N = c.frames * m->S;
+  m->Ns = m->N + (c.attn_mode == FC_ATTN_FULL3D_CONCAT ? c.text_len : 0);
+  m->pd = c.patch * c.patch * c.channels;
+  m->hd = hd;
+  m->nmod = c.attn_mode == FC_ATTN_FACTORIZED_CROSS ? 9 : 6;
+  *out = m;
+  return FC_OK;
+}
+
+int fc_model_weight_count(const fc_model* m, size_t* out) {
+  if (!m || !out) return fail(FC_ERR_NULL, "NULL argument");
+  *out = weight_count(m->cfg);
+  return FC_OK;
+}
+
+int fc_model_set_weights(fc_model* m, const float* blob, size_t n_floats) {
+  if (!m || !blob) return fail(FC_ERR_NULL, "NULL argument");
+  if (n_floats != weight_count(m->cfg)) return fail(FC_ERR_SHAPE, "weight blob has the wrong number of floats");
+  const fc_model_config& c = m->cfg;
+  const int D = c.hidden;
+  if (m->wbuf) { (void)hipFree(m->wbuf); m->wbuf = nullptr; m->has_weights = false; }
+  m->wbytes = layout_weights(m, nullptr);
+  HIP_TRY(hipMalloc((void**)&m->wbuf, m->wbytes));
+  layout_weights(m, m->wbuf);
+
+  // staging buffer for one tensor at a time (largest matrix of the model)
+  size_t big = (size_t)D * std::max(std::max(3 * D, c.mlp_dim), std::max(c.text_dim, m->nmod * D));
+  big = std::max(big, (size_t)c.t_embed_dim * D);
+  float* stage = nullptr;
+  HIP_TRY(hipMalloc((void**)&stage, big * 4));
+  size_t off = 0;
+  int rc = FC_OK;
+  auto up_matrix_t = [&](void* dst, int in, int out) -> hipError_t {   // blob [in,out] -> device [out,in] act dtype
+    hipError_t e = hipMemcpy(stage, blob + off, (size_t)in * out * 4, hipMemcpyHostToDevice);
+    if (e != hipSuccess) return e;
+    off += (size_t)in * out;
+    e = launch_transpose_convert(stage, dst, in, out, m->bf16, nullptr);
+    if (e != hipSuccess) return e;
+    return hipDeviceSynchronize();
+  };
+  auto up_f32 = [&](float* dst, size_t n) -> hipError_t {
+    hipError_t e = hipMemcpy(dst, blob + off, n * 4, hipMemcpyHostToDevice);
+    off += n;
+    return e;
+  };
+  auto up_lin = [&](Linear& L) -> hipError_t {
+    hipError_t e = up_matrix_t(L.wt, L.in, L.out);
+    if (e != hipSuccess) return e;
+    return up_f32(L.b, L.out);
+  };
+#define UP(expr)                                                          \
+  do {                                                                    \
+    hipError_t _e = (expr);                                               \
+    if (_e != hipSuccess) { rc = fail_hip(_e, #expr); goto done; }        \
+  } while (0)
+  UP(up_lin(m->t1));
+  UP(up_lin(m->t2));
+  UP(up_lin(m->y));
+  UP(up_f32(m->p_w, (size_t)m->pd * D));
+  UP(up_f32(m->p_b, D));
+  for (int l = 0; l < c.depth; ++l) {
+    Block& b = m->blocks[l];
+    const size_t nm = (size_t)m->nmod * D;
+    UP(up_matrix_t((unsigned char*)m->mod_w + (size_t)l * nm * D * m->esz, D, (int)nm));
+    UP(up_f32(m->mod_b + (size_t)l * nm, nm));
+    UP(up_lin(b.qkv[0]));
+    UP(up_lin(b.proj[0]));
+    if (c.attn_mode == FC_ATTN_FACTORIZED_CROSS) {
+      UP(up_lin(b.qkv[1]));
+      UP(up_lin(b.proj[1]));
+      UP(up_lin(b.xq));
+      UP(up_lin(b.xkv));
+      UP(up_lin(b.xproj));
+    }
+    UP(up_lin(b.fc1));
+    UP(up_lin(b.fc2));
+  }
+  UP(up_lin(m->fmod));
+  UP(up_lin(m->fout));
+  {
+    // positional tables, computed in double: spatial [S, D] = [sincos(h') | sincos(w')], temporal [T, D]
+    const int gw = c.width / c.patch;
+    std::vector<float> sp((size_t)m->S * D), tp((size_t)c.frames * D);
+    for (int s = 0; s < m->S; ++s) {
+      sincos_1d((double)(s / gw), D / 2, &sp[(size_t)s * D]);
+      sincos_1d((double)(s % gw), D / 2, &sp[(size_t)s * D + D / 2]);
+    }
+    for (int t = 0; t < c.frames; ++t) sincos_1d((double)t, D, &tp[(size_t)t * D]);
+    UP(hipMemcpy(m->pos_sp, sp.data(), sp.size() * 4, hipMemcpyHostToDevice));
+    UP(hipMemcpy(m->pos_t, tp.data(), tp.size() * 4, hipMemcpyHostToDevice));
+  }
+  UP(hipDeviceSynchronize());
+  m->has_weights = true;
+done:
+#undef UP
+  (void)hipFree(stage);
+  return rc;
+}
+
+int fc_model_destroy(fc_model* m) {
+  if (!m) return FC_OK;
+  if (m->wbuf) (void)hipFree(m->wbuf);
+  delete m;
+  return FC_OK;
+}
+
+int fc_workspace_bytes(const fc_model* m, int32_t R, int32_t use_cfg, size_t* out) {
+  if (!m || !out) return fail(FC_ERR_NULL, "NULL argument");
+  if (R < 1) return fail(FC_ERR_RANGE, "batch_requests must be >= 1");
+  *out = carve(m, R, use_cfg != 0, nullptr).bytes;
+  return FC_OK;
+}
+
+int fc_denoise_step(fc_model* m, float* latent, const float* cond, const float* null_cond, const fc_schedule* sched,
+                    int32_t step, int32_t R, float* eps_out, void* workspace, size_t workspace_bytes, void* stream) {
+  Ctx ctx;
+  int rc = check_call(m, latent, cond, sched, R, workspace, workspace_bytes, null_cond != nullptr, &ctx, stream);
+  if (rc != FC_OK) return rc;
+  if (step < 1 || step > sched->num_steps) return fail(FC_ERR_RANGE, "step must be in 1..num_steps");
+  if ((rc = prepare(ctx, cond, null_cond)) != FC_OK) return rc;
+  return run_step(ctx, latent, sched, step, eps_out);
+}
+
+int fc_denoise_resume(fc_model* m, float* latent, const float* cond, const float* null_cond,
+                      const fc_schedule* sched, int32_t k, int32_t R, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+  Ctx ctx;
+  int rc = check_call(m, latent, cond, sched, R, workspace, workspace_bytes, null_cond != nullptr, &ctx, stream);
+  if (rc != FC_OK) return rc;
+  if (k < 0 || k > sched->num_steps) return fail(FC_ERR_RANGE, "k must be in 0..num_steps");
+  if (k == sched->num_steps) return FC_OK;
+  if ((rc = prepare(ctx, cond, null_cond)) != FC_OK) return rc;
+  for (int s = k + 1; s <= sched->num_steps; ++s)
+    if ((rc = run_step(ctx, latent, sched, s, nullptr)) != FC_OK) return rc;
+  return FC_OK;
+}
+
+int fc_schedule_coefficients(const fc_schedule* sched, int32_t step, float* out4, int32_t* t_out) {
+  if (!out4) return fail(FC_ERR_NULL, "NULL argument");
+  int t = 0;
+  int rc = step_coefficients(sched, step, out4, &t);
+  if (rc == FC_OK && t_out) *t_out = t;
+  return rc;
+}
+
+const char* fc_status_string(int status) {
+  switch (status) {
+    case FC_OK: return "ok";
+    case FC_ERR_NULL: return "null pointer";
+    case FC_ERR_SHAPE: return "bad shape or configuration";
+    case FC_ERR_RANGE: return "argument out of range";
+    case FC_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case FC_ERR_DEVICE: return "HIP error";
+    case FC_ERR_UNSUPPORTED: return "unsupported";
+    case FC_ERR_STATE: return "weights not set";
+  }
+  return "unknown status";
+}
+
+const char* fc_last_error(void) { return g_err.c_str(); }
+
+// ---------------------------------------------------------------- single operators
+int fc_op_linear(int32_t dtype, const void* A, const void* Wt, const float* bias, void* out, int32_t M, int32_t N,
+                 int32_t K, int32_t epilogue, void* stream) {
+  if (!A || !Wt || !out) return fail(FC_ERR_NULL, "NULL argument");
+  if (M < 0 || N < 0 || K < 0 || (epilogue != 0 && epilogue != 1)) return fail(FC_ERR_RANGE, "bad size or epilogue");
+  EpiParams ep;
+  ep.bias = bias; ep.out = out; ep.ldo = N;
+  HIP_TRY(launch_gemm(dtype == FC_BF16, epilogue ? EPI_GELU : EPI_STORE, A, Wt, M, N, K, ep, (hipStream_t)stream));
+  return FC_OK;
+}
+
+int fc_op_linear_residual(int32_t dtype, const void* A, const void* Wt, const float* bias, const float* gate,
+                          float* x, int32_t M, int32_t N, int32_t K, void* stream) {
+  if (!A || !Wt || !x) return fail(FC_ERR_NULL, "NULL argument");
+  if (M < 0 || N < 0 || K < 0) return fail(FC_ERR_RANGE, "bad size");
+  EpiParams ep;
+  ep.bias = bias; ep.x = x; ep.ldo = N; ep.gate = gate;
+  HIP_TRY(launch_gemm(dtype == FC_BF16, EPI_RESID, A, Wt, M, N, K, ep, (hipStream_t)stream));
+  return FC_OK;
+}
+
+int fc_op_attention(int32_t dtype, const void* q, const void* k, const void* vt, void* out, int32_t G, int32_t nq,
+                    int32_t nk, int32_t d, int32_t impl, void* stream) {
+  if (!q || !k || !vt || !out) return fail(FC_ERR_NULL, "NULL argument");
+  if (G < 0 || nq < 0 || nk < 1 || d < 1) return fail(FC_ERR_RANGE, "bad size");
+  AttnParams ap{};
+  ap.q = q; ap.k = k; ap.vt = vt; ap.out = out;
+  ap.B = G; ap.heads = 1; ap.hd = d;
+  ap.groups = 1; ap.nq = nq; ap.nk = nk;
+  ap.q_tokens = nq; ap.q_gstride = 0; ap.q_istride = 1;
+  ap.k_tokens = nk; ap.k_tokens_pad = (int)round_up(nk, 64); ap.k_gstride = 0; ap.k_istride = 1;
+  ap.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)d));
+  hipError_t e = launch_attention(dtype == FC_BF16, ap, impl, (hipStream_t)stream);
+  if (e == hipErrorInvalidValue) return fail(FC_ERR_UNSUPPORTED, "head dim not supported");
+  HIP_TRY(e);
+  return FC_OK;
+}
+
+int fc_op_layernorm_modulate(int32_t dtype, const float* x, const float* shift, const float* scale, void* out,
+                             int32_t M, int32_t D, float eps, void* stream) {
+  if (!x || !out) return fail(FC_ERR_NULL, "NULL argument");
+  if ((shift == nullptr) != (scale == nullptr)) return fail(FC_ERR_NULL, "shift and scale go together");
+  if (M < 0 || D < 4 || D % 4) return fail(FC_ERR_RANGE, "D must be a positive multiple of 4");
+  HIP_TRY(launch_ln_modulate(dtype == FC_BF16, x, shift, scale, out, M, D, eps, M > 0 ? M : 1, M > 0 ? M : 1, 0,
+                             (hipStream_t)stream));
+  return FC_OK;
+}
+
+int fc_op_cfg_ddim(float* x, const float* eps_c, const float* eps_u, float* eps_out, size_t n, float gs,
+                   const float* coef4, void* stream) {
+  if (!x || !eps_c || !coef4) return fail(FC_ERR_NULL, "NULL argument");
+  HIP_TRY(launch_cfg_ddim(x, eps_c, eps_u, eps_out, n, gs, coef4[0], coef4[1], coef4[2], coef4[3],
+                          (hipStream_t)stream));
+  return FC_OK;
+}
+
+}  // extern "C"

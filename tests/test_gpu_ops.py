@@ -1,0 +1,190 @@
+"""Per-kernel parity: each operator of the step, called through the C ABI, against
+the matching piece of the CPU oracle on the same seeded inputs."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import dit, sampler
+from paper_2501_04012_amd import synth
+from util import dev, host, max_abs, rel_l2
+
+pytestmark = pytest.mark.gpu
+BF = synth.round_to_bf16
+
+
+def _torch():
+    import torch
+    return torch
+
+
+# --------------------------------------------------------------------------- linear layers
+
+LIN_SHAPES = [
+    (1, 32, 64), (300, 200, 128), (513, 384, 256), (64, 1152, 1152), (127, 96, 64),
+    (8209, 2048, 128),       # enough tiles for the 256x128 configuration, ragged M
+    (250, 160, 72),          # K not a multiple of 64: plain kernel
+]
+
+
+@pytest.mark.parametrize("M,N,K", LIN_SHAPES)
+@pytest.mark.parametrize("epilogue", [0, 1])
+def test_linear_bf16(fc, M, N, K, epilogue):
+    torch = _torch()
+    rng = np.random.default_rng(M * 7 + N * 3 + K)
+    A = BF(rng.standard_normal((M, K), dtype=np.float32))
+    W = BF(rng.standard_normal((K, N), dtype=np.float32) * np.float32(1 / math.sqrt(K)))
+    b = rng.standard_normal(N, dtype=np.float32)
+    want = A.astype(np.float64) @ W.astype(np.float64) + b
+    if epilogue:
+        want = dit.gelu_tanh(want)
+    out = torch.empty((M, N), dtype=torch.bfloat16, device="cuda:0")
+    fc.fc_op_linear(fc.FC_BF16, dev(A, True), dev(W.T.copy(), True), dev(b), out, M, N, K, epilogue)
+    torch.cuda.synchronize()
+    got = host(out)
+    assert rel_l2(got, want) < 4e-3, (rel_l2(got, want), max_abs(got, want))
+    assert max_abs(got, want) < 3e-2
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (70, 65, 33), (256, 64, 64)])
+def test_linear_fp32(fc, M, N, K):
+    torch = _torch()
+    rng = np.random.default_rng(M + N + K)
+    A = rng.standard_normal((M, K), dtype=np.float32)
+    W = rng.standard_normal((K, N), dtype=np.float32)
+    b = rng.standard_normal(N, dtype=np.float32)
+    out = torch.empty((M, N), dtype=torch.float32, device="cuda:0")
+    fc.fc_op_linear(fc.FC_F32, dev(A), dev(W.T.copy()), dev(b), out, M, N, K, 1)
+    torch.cuda.synchronize()
+    want = dit.gelu_tanh(A.astype(np.float64) @ W.astype(np.float64) + b)
+    assert rel_l2(host(out), want) < 1e-5
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("gated", [True, False])
+def test_linear_residual(fc, dtype, gated):
+    torch = _torch()
+    M, N, K = 333, 192, 128
+    rng = np.random.default_rng(5)
+    bf = dtype == "bf16"
+    A = rng.standard_normal((M, K), dtype=np.float32)
+    W = rng.standard_normal((K, N), dtype=np.float32) * np.float32(0.1)
+    if bf:
+        A, W = BF(A), BF(W)
+    b = rng.standard_normal(N, dtype=np.float32)
+    g = rng.standard_normal(N, dtype=np.float32) if gated else None
+    x = rng.standard_normal((M, N), dtype=np.float32)
+    want = x + (g if gated else 1.0) * (A.astype(np.float64) @ W.astype(np.float64) + b)
+    dx = dev(x)
+    fc.fc_op_linear_residual(fc.FC_BF16 if bf else fc.FC_F32, dev(A, bf), dev(W.T.copy(), bf), dev(b),
+                             dev(g) if gated else None, dx, M, N, K)
+    torch.cuda.synchronize()
+    assert rel_l2(host(dx), want) < (1e-5 if not bf else 1e-5)   # fp32 accumulate, fp32 output in both
+
+
+# --------------------------------------------------------------------------- attention
+
+def _attn_case(fc, G, nq, nk, d, gain, bf, impl):
+    torch = _torch()
+    qs, ks, vs = [], [], []
+    for g in range(G):
+        q, k, v = synth.sharp_qkv(1000 + 17 * g + nq + nk + d, nq, nk, d, gain=gain)
+        qs.append(q); ks.append(k); vs.append(v)
+    q, k, v = np.stack(qs), np.stack(ks), np.stack(vs)
+    if bf:
+        q, k, v = BF(q), BF(k), BF(v)
+    nkp = (nk + 63) // 64 * 64
+    vt = np.full((G, d, nkp), np.nan, dtype=np.float32)       # poison the padding: it must be ignored
+    vt[:, :, :nk] = v.transpose(0, 2, 1)
+    want = dit.attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64))
+    out = torch.full((G, nq, d), float("nan"), dtype=torch.bfloat16 if bf else torch.float32, device="cuda:0")
+    fc.fc_op_attention(fc.FC_BF16 if bf else fc.FC_F32, dev(q, bf), dev(k, bf), dev(vt, bf), out, G, nq, nk, d, impl)
+    torch.cuda.synchronize()
+    return host(out), want
+
+
+@pytest.mark.parametrize("G,nq,nk,d", [(3, 300, 333, 64), (2, 64, 64, 64), (1, 1, 1, 64), (2, 257, 120, 72),
+                                       (1, 700, 1000, 64), (4, 256, 256, 72), (1, 33, 7, 72)])
+@pytest.mark.parametrize("gain", [1.0, 2.5])
+def test_attention_flash_bf16(fc, G, nq, nk, d, gain):
+    got, want = _attn_case(fc, G, nq, nk, d, gain, True, 0)
+    assert np.all(np.isfinite(got))
+    assert rel_l2(got, want) < 1e-2, (rel_l2(got, want), max_abs(got, want))
+    assert max_abs(got, want) < 5e-2
+
+
+@pytest.mark.parametrize("G,nq,nk,d,bf", [(2, 50, 70, 16, False), (3, 16, 16, 72, True), (1, 100, 130, 64, True),
+                                          (2, 9, 5, 8, False), (1, 20, 40, 128, False)])
+def test_attention_plain(fc, G, nq, nk, d, bf):
+    got, want = _attn_case(fc, G, nq, nk, d, 2.0, bf, 1)
+    assert rel_l2(got, want) < (5e-3 if bf else 2e-5)
+
+
+def test_attention_rows_are_convex_combinations(fc):
+    """Property that holds at any size: with all-ones V every output is exactly 1
+    (softmax rows sum to 1), also across a ragged last key tile."""
+    torch = _torch()
+    G, nq, nk, d = 2, 130, 1000, 64
+    q, k, _ = synth.sharp_qkv(3, nq, nk, d, gain=2.0)
+    q, k = np.stack([BF(q)] * G), np.stack([BF(k)] * G)
+    vt = np.ones((G, d, 1024), dtype=np.float32)
+    out = torch.empty((G, nq, d), dtype=torch.bfloat16, device="cuda:0")
+    fc.fc_op_attention(fc.FC_BF16, dev(q, True), dev(k, True), dev(vt, True), out, G, nq, nk, d, 0)
+    torch.cuda.synchronize()
+    np.testing.assert_allclose(host(out), 1.0, atol=8e-3)
+
+
+# --------------------------------------------------------------------------- LayerNorm + modulate
+
+@pytest.mark.parametrize("M,D", [(1, 64), (37, 1152), (130, 3072), (5, 4)])
+@pytest.mark.parametrize("bf", [False, True])
+@pytest.mark.parametrize("mod", [True, False])
+def test_layernorm_modulate(fc, M, D, bf, mod):
+    torch = _torch()
+    rng = np.random.default_rng(M + D)
+    x = rng.standard_normal((M, D), dtype=np.float32) * 3 + 1
+    sh = rng.standard_normal(D, dtype=np.float32) if mod else None
+    sc = rng.standard_normal(D, dtype=np.float32) if mod else None
+    want = dit.layernorm(x.astype(np.float64), 1e-6)
+    if mod:
+        want = dit.modulate(want, sh, sc)
+    out = torch.empty((M, D), dtype=torch.bfloat16 if bf else torch.float32, device="cuda:0")
+    fc.fc_op_layernorm_modulate(fc.FC_BF16 if bf else fc.FC_F32, dev(x), dev(sh) if mod else None,
+                                dev(sc) if mod else None, out, M, D, 1e-6)
+    torch.cuda.synchronize()
+    assert rel_l2(host(out), want) < (4e-3 if bf else 2e-6)
+
+
+# --------------------------------------------------------------------------- guidance + DDIM
+
+@pytest.mark.parametrize("n", [1, 7, 4096, 65536 + 3])
+@pytest.mark.parametrize("guided", [True, False])
+def test_cfg_ddim(fc, n, guided):
+    torch = _torch()
+    rng = np.random.default_rng(n)
+    x, ec, eu = (rng.standard_normal(n, dtype=np.float32) for _ in range(3))
+    sched = synth.Schedule()
+    coef, _ = fc.fc_schedule_coefficients(sched, 25)
+    _, a_t, a_p = sampler.step_coefficients(sched, 25)
+    e = sampler.guide(ec.astype(np.float64), eu.astype(np.float64), 7.5) if guided else ec.astype(np.float64)
+    want = sampler.ddim_update(x.astype(np.float64), e, a_t, a_p)
+    dx, de = dev(x), torch.empty(n, dtype=torch.float32, device="cuda:0")
+    fc.fc_op_cfg_ddim(dx, dev(ec), dev(eu) if guided else None, de, n, 7.5, coef)
+    torch.cuda.synchronize()
+    assert rel_l2(host(dx), want) < 1e-6
+    assert rel_l2(host(de), e) < 1e-6
+
+
+def test_cfg_ddim_misaligned_pointers(fc):
+    torch = _torch()
+    n = 1001
+    rng = np.random.default_rng(1)
+    x, ec = rng.standard_normal(n + 1, dtype=np.float32), rng.standard_normal(n + 1, dtype=np.float32)
+    coef, _ = fc.fc_schedule_coefficients(synth.Schedule(), 50)
+    _, a_t, a_p = sampler.step_coefficients(synth.Schedule(), 50)
+    dx, de = dev(x), dev(ec)
+    fc.fc_op_cfg_ddim(dx[1:], de[1:], None, None, n, 1.0, coef)     # 4-byte aligned only
+    torch.cuda.synchronize()
+    got = host(dx)
+    assert got[0] == x[0]
+    assert rel_l2(got[1:], sampler.ddim_update(x[1:].astype(np.float64), ec[1:].astype(np.float64), a_t, a_p)) < 1e-6

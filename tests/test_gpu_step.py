@@ -1,0 +1,179 @@
+"""Parity of fc_denoise_step / fc_denoise_resume (through the C ABI) against the CPU
+oracle on the seeded workloads, plus API error paths and the resume invariants the
+paper states (a hit runs the same step function, only later: Sec. 2.2, Sec. 3.2)."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from oracle import dit, sampler
+from paper_2501_04012_amd import synth
+from util import dev, host, max_abs, rel_l2, run_step_gpu
+
+pytestmark = pytest.mark.gpu
+
+# tolerances of the parity bar: bf16 rel-L2 <= 1e-2 and max-abs <= 5e-2 per step; fp32 rel-L2 <= 1e-4
+BF16_REL, BF16_ABS, F32_REL = 1e-2, 5e-2, 1e-4
+
+
+def oracle_step(w, cfg, W, inputs, step, dtype=np.float64):
+    lat, cond, null = inputs
+    return sampler.denoise_step(cfg, W, lat, cond, null, w.schedule, step, dtype=dtype, return_eps=True)
+
+
+def check(got_lat, got_eps, want_lat, want_eps, bf16):
+    rl, re_ = rel_l2(got_lat, want_lat), rel_l2(got_eps, want_eps)
+    ma = max_abs(got_lat, want_lat)
+    if bf16:
+        assert rl <= BF16_REL and ma <= BF16_ABS, (rl, ma, re_)
+        assert re_ <= 2e-2, re_          # the noise estimate itself, not diluted by the latent
+    else:
+        assert rl <= F32_REL and re_ <= F32_REL, (rl, re_)
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg3b"])
+def test_tiny_fp32_configs(fc, name):
+    w = synth.WORKLOADS[name]
+    W = synth.make_weights(w.model, w.weight_seed)
+    inputs = synth.workload_inputs(w)
+    got = run_step_gpu(fc, w, weights=W, inputs=inputs)
+    want = oracle_step(w, w.model, W, inputs, w.step)
+    check(*got, *want, bf16=False)
+
+
+@pytest.mark.parametrize("mode", [synth.ATTN_FACTORIZED_CROSS, synth.ATTN_FULL3D_CONCAT])
+@pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
+def test_small_ragged_model_with_sharp_softmax(fc, mode, dtype):
+    """A small model whose token counts are not multiples of any tile, weights large
+    enough that softmax rows are peaked, guidance on, two requests."""
+    cfg = synth.ModelConfig(frames=3, height=12, width=20, channels=4, patch=2, hidden=256, heads=4, mlp_dim=512,
+                            depth=2, text_len=26, text_dim=96, attn_mode=mode, dtype=dtype)
+    w = synth.Workload("small", cfg, weight_seed=7, latent_seed=8, text_seed=9, null_seed=10, requests=2)
+    W = synth.make_weights(cfg, 7, std=0.08)
+    inputs = synth.workload_inputs(w)
+    got = run_step_gpu(fc, w, weights=W, inputs=inputs)
+    want = oracle_step(w, cfg, W, inputs, w.step)
+    check(*got, *want, bf16=dtype == synth.DT_BF16)
+
+
+def test_cfg2_bf16_factorized_block(fc):
+    w = synth.WORKLOADS["cfg2"]
+    W = synth.make_weights(w.model, w.weight_seed)
+    inputs = synth.workload_inputs(w)
+    got = run_step_gpu(fc, w, weights=W, inputs=inputs)
+    want = oracle_step(w, w.model, W, inputs, w.step)
+    check(*got, *want, bf16=True)
+
+
+def test_cfg4_bf16_full3d_block_sampled_rows(fc):
+    """Full-size full-3D block: the oracle evaluates sampled video-token rows (keys and
+    values of all 17 776 tokens, queries of the sample), the GPU the whole step."""
+    w = synth.WORKLOADS["cfg4"]
+    cfg = w.model
+    W = synth.make_weights(cfg, w.weight_seed)
+    inputs = synth.workload_inputs(w)
+    lat, cond, _ = inputs
+    got_lat, got_eps = run_step_gpu(fc, w, weights=W, inputs=inputs)
+    rows = np.random.default_rng(0).choice(cfg.video_tokens, size=96, replace=False)
+    rows = np.concatenate([rows, [0, cfg.video_tokens - 1, 17549 - 45]])
+    want = dit.forward(cfg, W, lat[0], cond[0], 500, dtype=np.float32, video_rows=rows)
+    got = dit.patchify(got_eps[0], cfg.patch)[rows]
+    assert rel_l2(got, want) <= 2e-2, rel_l2(got, want)
+    assert max_abs(got, want) <= BF16_ABS
+    # latent update on those patches
+    _, a_t, a_p = sampler.step_coefficients(w.schedule, w.step)
+    want_lat = sampler.ddim_update(dit.patchify(lat[0].astype(np.float64), cfg.patch)[rows], want, a_t, a_p)
+    got_l = dit.patchify(got_lat[0], cfg.patch)[rows]
+    assert rel_l2(got_l, want_lat) <= BF16_REL and max_abs(got_l, want_lat) <= BF16_ABS
+
+
+def test_cfg3a_bf16_stack_depth4_with_guidance(fc):
+    w = synth.WORKLOADS["cfg3a"]
+    cfg = replace(w.model, depth=4)
+    W = synth.make_weights(cfg, w.weight_seed)
+    inputs = synth.workload_inputs(w)
+    got = run_step_gpu(fc, w, depth=4, weights=W, inputs=inputs)
+    want = oracle_step(w, cfg, W, inputs, w.step, dtype=np.float32)
+    check(*got, *want, bf16=True)
+
+
+def test_cfg5b_resume_trajectory_and_invariants(fc):
+    import torch
+    w = synth.WORKLOADS["cfg5b"]
+    cfg = w.model
+    W = synth.make_weights(cfg, w.weight_seed)
+    lat, cond, null = synth.workload_inputs(w)
+    den = fc.Denoiser(cfg, W, w.requests, True)
+    try:
+        d_cond, d_null = dev(cond), dev(null)
+        finals = {}
+        for k in w.resume_k:
+            d_lat = dev(lat)
+            den.resume(d_lat, d_cond, d_null, w.schedule, k)
+            torch.cuda.synchronize()
+            finals[k] = host(d_lat)
+            want = sampler.denoise_resume(cfg, W, lat, cond, null, w.schedule, k)
+            assert rel_l2(finals[k], want) <= 1e-3, (k, rel_l2(finals[k], want))
+        # a hit at k followed by single steps == one resume call, bit for bit
+        d_lat = dev(lat)
+        for s in range(11, 21):
+            den.step(d_lat, d_cond, d_null, w.schedule, s)
+        den.resume(d_lat, d_cond, d_null, w.schedule, 20)
+        torch.cuda.synchronize()
+        d_ref = dev(lat)
+        den.resume(d_ref, d_cond, d_null, w.schedule, 10)
+        torch.cuda.synchronize()
+        assert torch.equal(d_lat, d_ref)
+        # run-to-run determinism
+        assert np.array_equal(host(d_ref), finals[10])
+        # k = N: untouched
+        d_lat = dev(lat)
+        den.resume(d_lat, d_cond, d_null, w.schedule, 50)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(d_lat), lat)
+    finally:
+        den.close()
+
+
+def test_api_errors(fc):
+    import torch
+    w = synth.WORKLOADS["cfg1"]
+    cfg = w.model
+    with pytest.raises(fc.FlexDenoiseError) as e:
+        fc.fc_model_create(replace(cfg, heads=5))
+    assert e.value.status == -2
+    with pytest.raises(fc.FlexDenoiseError) as e:
+        fc.fc_model_create(replace(cfg, height=7))
+    assert e.value.status == -2
+    m = fc.fc_model_create(cfg)
+    try:
+        lat, cond, _ = synth.workload_inputs(w)
+        d_lat, d_cond = dev(lat), dev(cond)
+        ws = torch.empty(fc.fc_workspace_bytes(m, 1, False), dtype=torch.uint8, device="cuda:0")
+        with pytest.raises(fc.FlexDenoiseError) as e:          # weights not set
+            fc.fc_denoise_step(m, d_lat, d_cond, None, w.schedule, 25, 1, None, ws)
+        assert e.value.status == -7
+        with pytest.raises(fc.FlexDenoiseError) as e:
+            fc.fc_model_set_weights(m, np.zeros(10, dtype=np.float32))
+        assert e.value.status == -2
+        fc.fc_model_set_weights(m, synth.pack_weights(cfg, synth.make_weights(cfg, w.weight_seed)))
+        for bad_step in (0, 51):
+            with pytest.raises(fc.FlexDenoiseError) as e:
+                fc.fc_denoise_step(m, d_lat, d_cond, None, w.schedule, bad_step, 1, None, ws)
+            assert e.value.status == -3
+        with pytest.raises(fc.FlexDenoiseError) as e:
+            fc.fc_denoise_resume(m, d_lat, d_cond, None, w.schedule, 51, 1, ws)
+        assert e.value.status == -3
+        with pytest.raises(fc.FlexDenoiseError) as e:
+            fc.fc_denoise_step(m, d_lat, d_cond, None, w.schedule, 25, 1, None, ws[:1024])
+        assert e.value.status == -4
+        with pytest.raises(fc.FlexDenoiseError) as e:
+            fc.fc_denoise_step(m, None, d_cond, None, w.schedule, 25, 1, None, ws)
+        assert e.value.status == -1
+        with pytest.raises(fc.FlexDenoiseError) as e:
+            fc.fc_denoise_step(m, d_lat, d_cond, None, replace(w.schedule, eta=1.0), 25, 1, None, ws)
+        assert e.value.status == -6
+        torch.cuda.synchronize()
+        assert np.array_equal(host(d_lat), lat)               # no failed call touched the latent
+    finally:
+        fc.fc_model_destroy(m)
