@@ -1,0 +1,174 @@
+#!/usr/bin/env python3
+"""Benchmark of the denoising hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4|cfg2|cfg3a|cfg5a]
+
+A step is one fc_denoise_step over one batch of synthetic input (text projection,
+timestep conditioning, patch embedding, every transformer block, output head,
+guidance and DDIM update), inputs resident in HBM.  Prints one JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0
+
+
+def cpu_baseline(w, weights, lat, cond):
+    """The oracle (fp32 arithmetic) on the host cores, on a bounded sample of the same
+    workload, converted to steps/s."""
+    from oracle import dit, sampler
+    from paper_2501_04012_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    cfg = w.model
+    W32 = {k: np.asarray(v, dtype=np.float32) for k, v in weights.items()}
+    if cfg.attn_mode == synth.ATTN_FULL3D_CONCAT and cfg.depth == 1:
+        # evaluate n1 and 2*n1 sampled query rows; the cost is affine in the row count
+        rng = np.random.default_rng(0)
+        n1 = 768
+        rows = rng.choice(cfg.video_tokens, size=2 * n1, replace=False)
+        t0 = time.perf_counter(); dit.forward(cfg, W32, lat[0], cond[0], 500, dtype=None, video_rows=rows[:n1])
+        t1 = time.perf_counter(); dit.forward(cfg, W32, lat[0], cond[0], 500, dtype=None, video_rows=rows)
+        t2 = time.perf_counter()
+        a, b = (t1 - t0), (t2 - t1)
+        per_row = max(b - a, 0.0) / n1
+        fixed = max(a - per_row * n1, 0.0)
+        step_s = fixed + per_row * cfg.video_tokens
+        sample = (f"fp32 oracle forward of the block on {n1} and {2 * n1} sampled query rows (keys/values of all "
+                  f"{cfg.seq_tokens} tokens), extrapolated affinely to {cfg.video_tokens} rows; measured "
+                  f"{a:.1f}s + {b:.1f}s")
+    else:
+        # one forward of one sample through min(depth, 2) blocks, scaled to depth and batch
+        from dataclasses import replace
+        d = min(cfg.depth, 2)
+        cfg_s = replace(cfg, depth=d)
+        Ws = {k: v for k, v in W32.items() if not k.startswith("blk") or int(k[3:k.index(".")]) < d}
+        t0 = time.perf_counter(); dit.forward(cfg_s, Ws, lat[0].astype(np.float32), cond[0].astype(np.float32), 500,
+                                              dtype=None)
+        t1 = time.perf_counter()
+        forwards = lat.shape[0] * (2 if w.null_seed is not None else 1)
+        step_s = (t1 - t0) * (cfg.depth / d) * forwards
+        sample = (f"fp32 oracle forward of one sample through {d} of {cfg.depth} blocks ({t1 - t0:.1f}s), "
+                  f"scaled by depth and by {forwards} forwards per step")
+    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": int(cores), "kind": "oracle", "sample": sample}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2501_04012_amd as fc
+    from paper_2501_04012_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    cfg = w.model
+    weights = synth.make_weights(cfg, w.weight_seed)
+    lat, cond, null = synth.workload_inputs(w)
+    R = lat.shape[0]
+    use_cfg = null is not None
+    den = fc.Denoiser(cfg, weights, R, use_cfg)
+    d_lat0 = torch.from_numpy(lat).cuda()
+    d_cond = torch.from_numpy(cond).cuda()
+    d_null = torch.from_numpy(null).cuda() if use_cfg else None
+    d_lat = d_lat0.clone()
+
+    for _ in range(args.warmup):
+        d_lat.copy_(d_lat0)
+        den.step(d_lat, d_cond, d_null, w.schedule, w.step)
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps; the dominant kernel is bracketed by HIP events on the same stream
+    fc.fc_profile_enable(den.model, True)
+    d_lat.copy_(d_lat0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        den.step(d_lat, d_cond, d_null, w.schedule, w.step)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = fc.fc_profile_read(den.model)
+    fc.fc_profile_enable(den.model, False)
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    forwards = R * (2 if use_cfg else 1)
+    fl = synth.forward_flops(cfg)
+    step_flops = fl["total"] * forwards
+    tflops = step_flops / (ms_per_step * 1e-3) / 1e12
+
+    kernels = {}
+    for name, (ms, cnt) in prof.items():
+        if cnt:
+            kernels[name] = {"ms_per_step": ms / args.steps, "avg_launch_ms": ms / cnt, "launches": int(cnt)}
+    # dominant kernel: the category with the most time
+    dom = max(kernels, key=lambda k: kernels[k]["ms_per_step"])
+    per_launch_flops = {
+        "attn_full3d": fl["block_attention"] * forwards,
+        "attn_spatial": 4.0 * cfg.video_tokens * cfg.spatial_tokens * cfg.hidden * forwards,
+        "attn_cross": 4.0 * cfg.video_tokens * cfg.text_len * cfg.hidden * forwards,
+        "gemm_qkv": 2.0 * cfg.seq_tokens * cfg.hidden * 3 * cfg.hidden * forwards,
+        "gemm_fc1": 2.0 * cfg.seq_tokens * cfg.hidden * cfg.mlp_dim * forwards,
+        "gemm_fc2": 2.0 * cfg.seq_tokens * cfg.hidden * cfg.mlp_dim * forwards,
+        "gemm_proj": 2.0 * cfg.seq_tokens * cfg.hidden * cfg.hidden * forwards,
+    }
+    for k, f in per_launch_flops.items():
+        if k in kernels:
+            kernels[k]["tflops"] = f / (kernels[k]["avg_launch_ms"] * 1e-3) / 1e12
+    if dom in per_launch_flops:
+        ach = per_launch_flops[dom] / (kernels[dom]["avg_launch_ms"] * 1e-3) / 1e12
+        roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": ach / PEAK_BF16_TFLOPS, "traffic": None}
+    else:
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": None, "traffic": None}
+
+    out = {
+        "metric": "denoising steps/s per video + attention/GEMM TFLOP/s (% of MI355X bf16 peak)",
+        "value": 1e3 / ms_per_step, "unit": "steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == synth.DT_BF16 else "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "requests": R, "guidance_pair": use_cfg,
+                   "tokens": cfg.seq_tokens, "hidden": cfg.hidden, "heads": cfg.heads, "depth": cfg.depth,
+                   "attn_mode": "full3d_concat" if cfg.attn_mode else "factorized_cross"},
+        "video_steps_per_s": R * 1e3 / ms_per_step,
+        "tflops": tflops, "pct_bf16_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
+        "step_tflop": step_flops / 1e12,
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+    den.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, weights, lat, cond)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -151,6 +151,17 @@ int fc_schedule_coefficients(const fc_schedule* sched, int32_t step, float* out4
 const char* fc_status_string(int status);
 const char* fc_last_error(void);
 
+/* ---- per-kernel timing.  While enabled, every launch group of a step is bracketed by a
+ * HIP event pair recorded on the call's stream.  fc_profile_read() waits for the
+ * recorded events, adds the elapsed milliseconds and the number of brackets per
+ * category into ms_out / launches_out (host arrays of n >= fc_profile_categories()
+ * entries) and clears the record.  Categories are named by
+ * fc_profile_category_name(i).  fc_profile_categories() returns the count, not a status. */
+int fc_profile_enable(fc_model* m, int32_t enable);
+int fc_profile_categories(void);
+const char* fc_profile_category_name(int32_t i);
+int fc_profile_read(fc_model* m, int32_t n, double* ms_out, int64_t* launches_out);
+
 /* ---- single operators of the step, exposed for per-kernel tests and timing.
  * All pointers dev; dtype FC_F32 -> float elements, FC_BF16 -> bfloat16 (uint16)
  * elements for every tensor marked "act". ------------------------------------- */

@@ -52,6 +52,9 @@ EXPORTS = {
     "fc_denoise_resume": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(fc_schedule), C.c_int32,
                           C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p],
     "fc_schedule_coefficients": [C.POINTER(fc_schedule), C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_int32)],
+    "fc_profile_enable": [C.c_void_p, C.c_int32],
+    "fc_profile_categories": [],
+    "fc_profile_read": [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)],
     "fc_op_linear": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                      C.c_int32, C.c_void_p],
     "fc_op_linear_residual": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
@@ -63,7 +66,7 @@ EXPORTS = {
     "fc_op_cfg_ddim": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_float,
                        C.POINTER(C.c_float), C.c_void_p],
 }
-_STRING_EXPORTS = {"fc_status_string": [C.c_int], "fc_last_error": []}
+_STRING_EXPORTS = {"fc_status_string": [C.c_int], "fc_last_error": [], "fc_profile_category_name": [C.c_int32]}
 
 
 def _load():
@@ -167,6 +170,27 @@ def fc_schedule_coefficients(sched: synth.Schedule, step: int):
     t = C.c_int32()
     _check(_lib.fc_schedule_coefficients(C.byref(s), step, out, C.byref(t)), "fc_schedule_coefficients")
     return np.array(list(out), dtype=np.float32), t.value
+
+
+def fc_profile_enable(model: int, enable: bool) -> None:
+    _check(_lib.fc_profile_enable(model, int(enable)), "fc_profile_enable")
+
+
+def fc_profile_categories() -> int:
+    return _lib.fc_profile_categories()
+
+
+def fc_profile_category_name(i: int) -> str:
+    return _lib.fc_profile_category_name(i).decode()
+
+
+def fc_profile_read(model: int):
+    """{category: (milliseconds, brackets)} since the last read."""
+    n = fc_profile_categories()
+    ms = (C.c_double * n)()
+    cnt = (C.c_int64 * n)()
+    _check(_lib.fc_profile_read(model, n, ms, cnt), "fc_profile_read")
+    return {fc_profile_category_name(i): (ms[i], cnt[i]) for i in range(n)}
 
 
 def fc_op_linear(dtype, A, Wt, bias, out, M, N, K, epilogue, stream=None) -> None:

@@ -30,6 +30,39 @@ int fail_hip(hipError_t e, const char* where) {
     if (_e != hipSuccess) return fail_hip(_e, #expr);         \
   } while (0)
 
+// Optional per-kernel timing: HIP event pairs recorded on the caller's stream around
+// each launch, summed per category when read.
+enum ProfCat : int {
+  PC_GEMM_QKV = 0, PC_GEMM_PROJ, PC_GEMM_FC1, PC_GEMM_FC2, PC_GEMM_OTHER,
+  PC_ATTN_SPATIAL, PC_ATTN_TEMPORAL, PC_ATTN_CROSS, PC_ATTN_FULL,
+  PC_LN_MODULATE, PC_PATCH_EMBED, PC_TIMESTEP_MOD, PC_CFG_DDIM, PC_OTHER, PC_COUNT
+};
+const char* const kProfNames[PC_COUNT] = {
+  "gemm_qkv", "gemm_proj", "gemm_fc1", "gemm_fc2", "gemm_other",
+  "attn_spatial", "attn_temporal", "attn_cross", "attn_full3d",
+  "ln_modulate", "patch_embed", "timestep_modulation", "cfg_ddim", "other"};
+
+struct Profiler {
+  bool on = false;
+  struct Rec { hipEvent_t a, b; int cat; };
+  std::vector<Rec> recs;
+  std::vector<hipEvent_t> pool;
+  hipEvent_t get() {
+    if (!pool.empty()) { hipEvent_t e = pool.back(); pool.pop_back(); return e; }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
+  void release_all() {
+    for (auto& r : recs) { pool.push_back(r.a); pool.push_back(r.b); }
+    recs.clear();
+  }
+  ~Profiler() {
+    release_all();
+    for (hipEvent_t e : pool) (void)hipEventDestroy(e);
+  }
+};
+
 struct Linear {           // weights [out, in] in the activation dtype, bias fp32
   void* wt = nullptr;
   float* b = nullptr;
@@ -62,6 +95,7 @@ struct fc_model {
   float* pos_sp = nullptr;         // [S, D]
   float* pos_t = nullptr;          // [T, D]
   std::vector<Block> blocks;
+  Profiler prof;
 };
 
 namespace {
@@ -231,8 +265,28 @@ struct Ctx {
   hipStream_t s;
 };
 
-int linear(const Ctx& c, int mode, const void* A, const Linear& L, int M, EpiParams ep) {
+struct ProfScope {        // records an event pair around the launches made in its lifetime
+  Profiler* p = nullptr;
+  hipStream_t s;
+  hipEvent_t a = nullptr, b = nullptr;
+  int cat;
+  ProfScope(const Ctx& c, int cat_) : s(c.s), cat(cat_) {
+    if (!c.m->prof.on) return;
+    p = &c.m->prof;
+    a = p->get(); b = p->get();
+    if (!a || !b) { p = nullptr; return; }
+    (void)hipEventRecord(a, s);
+  }
+  ~ProfScope() {
+    if (!p) return;
+    (void)hipEventRecord(b, s);
+    p->recs.push_back({a, b, cat});
+  }
+};
+
+int linear(const Ctx& c, int cat, int mode, const void* A, const Linear& L, int M, EpiParams ep) {
   ep.bias = L.b;
+  ProfScope ps(c, cat);
   HIP_TRY(launch_gemm(c.m->bf16, mode, A, L.wt, M, L.out, L.in, ep, c.s));
   return FC_OK;
 }
@@ -253,18 +307,21 @@ int prepare(const Ctx& c, const float* cond, const float* null_cond) {
   const fc_model_config& cf = m->cfg;
   const Workspace& w = c.w;
   const size_t per_text = (size_t)cf.text_len * cf.text_dim;
+  {
+  ProfScope ps(c, PC_OTHER);
   HIP_TRY(launch_convert_f32(cond, w.txt, per_text * c.R, m->bf16, c.s));
   if (c.use_cfg)
     HIP_TRY(launch_convert_f32(null_cond, (unsigned char*)w.txt + per_text * c.R * m->esz, per_text, m->bf16, c.s));
+  }
   EpiParams ep;
   ep.out = w.y; ep.ldo = cf.hidden;
-  int rc = linear(c, EPI_STORE, w.txt, m->y, w.NT * cf.text_len, ep);
+  int rc = linear(c, PC_GEMM_OTHER, EPI_STORE, w.txt, m->y, w.NT * cf.text_len, ep);
   if (rc != FC_OK) return rc;
   if (cf.attn_mode == FC_ATTN_FACTORIZED_CROSS) {
     for (int l = 0; l < cf.depth; ++l) {
       void* xk = (unsigned char*)w.xk + (size_t)l * w.NT * cf.text_len * cf.hidden * m->esz;
       void* xvt = (unsigned char*)w.xvt + (size_t)l * w.NT * w.Lp * cf.hidden * m->esz;
-      rc = linear(c, EPI_HEADS, w.y, m->blocks[l].xkv, w.NT * cf.text_len,
+      rc = linear(c, PC_GEMM_OTHER, EPI_HEADS, w.y, m->blocks[l].xkv, w.NT * cf.text_len,
                   heads_epi(c, nullptr, xk, xvt, 1, cf.text_len, w.Lp));
       if (rc != FC_OK) return rc;
     }
@@ -274,6 +331,7 @@ int prepare(const Ctx& c, const float* cond, const float* null_cond) {
 
 int ln_mod(const Ctx& c, const float* shift, const float* scale) {
   const fc_model* m = c.m;
+  ProfScope ps(c, PC_LN_MODULATE);
   HIP_TRY(launch_ln_modulate(m->bf16, c.w.x, shift, scale, c.w.u, c.w.B * m->Ns, m->cfg.hidden, m->cfg.ln_eps,
                              m->Ns, m->Ns, 0, c.s));
   return FC_OK;
@@ -285,7 +343,7 @@ int self_attention_branch(const Ctx& c, const Linear& qkv, const Linear& proj, c
   const fc_model_config& cf = m->cfg;
   const Workspace& w = c.w;
   const int rows = w.B * m->Ns;
-  int rc = linear(c, EPI_HEADS, w.u, qkv, rows, heads_epi(c, w.q, w.k, w.vt, 0, m->Ns, w.Nsp));
+  int rc = linear(c, PC_GEMM_QKV, EPI_HEADS, w.u, qkv, rows, heads_epi(c, w.q, w.k, w.vt, 0, m->Ns, w.Nsp));
   if (rc != FC_OK) return rc;
   AttnParams ap{};
   ap.q = w.q; ap.k = w.k; ap.vt = w.vt; ap.out = w.u;
@@ -296,10 +354,13 @@ int self_attention_branch(const Ctx& c, const Linear& qkv, const Linear& proj, c
   else { ap.groups = 1; ap.nq = ap.nk = m->Ns; ap.q_gstride = ap.k_gstride = 0; ap.q_istride = ap.k_istride = 1; }
   ap.kv_split = 0; ap.kv_shared_tail = 0;
   ap.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)m->hd));
-  HIP_TRY(launch_attention(m->bf16, ap, 0, c.s));
+  {
+    ProfScope ps(c, mode == 0 ? PC_ATTN_SPATIAL : mode == 1 ? PC_ATTN_TEMPORAL : PC_ATTN_FULL);
+    HIP_TRY(launch_attention(m->bf16, ap, 0, c.s));
+  }
   EpiParams ep;
   ep.x = w.x; ep.ldo = cf.hidden; ep.gate = gate;
-  return linear(c, EPI_RESID, w.u, proj, rows, ep);
+  return linear(c, PC_GEMM_PROJ, EPI_RESID, w.u, proj, rows, ep);
 }
 
 int cross_attention_branch(const Ctx& c, const Block& b, int layer) {
@@ -309,7 +370,7 @@ int cross_attention_branch(const Ctx& c, const Block& b, int layer) {
   const int rows = w.B * m->Ns;
   int rc = ln_mod(c, nullptr, nullptr);
   if (rc != FC_OK) return rc;
-  rc = linear(c, EPI_HEADS, w.u, b.xq, rows, heads_epi(c, w.q, nullptr, nullptr, 0, m->Ns, w.Nsp));
+  rc = linear(c, PC_GEMM_PROJ, EPI_HEADS, w.u, b.xq, rows, heads_epi(c, w.q, nullptr, nullptr, 0, m->Ns, w.Nsp));
   if (rc != FC_OK) return rc;
   AttnParams ap{};
   ap.q = w.q;
@@ -322,10 +383,13 @@ int cross_attention_branch(const Ctx& c, const Block& b, int layer) {
   ap.k_tokens = cf.text_len; ap.k_tokens_pad = w.Lp; ap.k_gstride = 0; ap.k_istride = 1;
   ap.kv_split = c.R; ap.kv_shared_tail = c.use_cfg;      // guidance rows all read the null text
   ap.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)m->hd));
-  HIP_TRY(launch_attention(m->bf16, ap, 0, c.s));
+  {
+    ProfScope ps(c, PC_ATTN_CROSS);
+    HIP_TRY(launch_attention(m->bf16, ap, 0, c.s));
+  }
   EpiParams ep;
   ep.x = w.x; ep.ldo = cf.hidden; ep.gate = nullptr;
-  return linear(c, EPI_RESID, w.u, b.xproj, rows, ep);
+  return linear(c, PC_GEMM_PROJ, EPI_RESID, w.u, b.xproj, rows, ep);
 }
 
 int mlp_branch(const Ctx& c, const Block& b, const float* mod) {
@@ -335,11 +399,11 @@ int mlp_branch(const Ctx& c, const Block& b, const float* mod) {
   if (rc != FC_OK) return rc;
   EpiParams e1;
   e1.out = c.w.hid; e1.ldo = m->cfg.mlp_dim;
-  rc = linear(c, EPI_GELU, c.w.u, b.fc1, rows, e1);
+  rc = linear(c, PC_GEMM_FC1, EPI_GELU, c.w.u, b.fc1, rows, e1);
   if (rc != FC_OK) return rc;
   EpiParams e2;
   e2.x = c.w.x; e2.ldo = D; e2.gate = mod + 2 * D;
-  return linear(c, EPI_RESID, c.w.hid, b.fc2, rows, e2);
+  return linear(c, PC_GEMM_FC2, EPI_RESID, c.w.hid, b.fc2, rows, e2);
 }
 
 // One forward pass of all B rows + guidance + DDIM update of the R latents.
@@ -354,20 +418,26 @@ int run_step(const Ctx& c, float* latent, const fc_schedule* sched, int step, fl
   if (rc != FC_OK) return rc;
 
   // conditioning: sinusoid -> Linear -> SiLU -> Linear -> c; every adaLN layer reads SiLU(c)
+  const int nm = m->nmod * D;
+  {
+  ProfScope ps(c, PC_TIMESTEP_MOD);
   HIP_TRY(launch_sinusoid((float)t, cf.t_embed_dim, w.e, c.s));
   HIP_TRY(launch_gemv(m->bf16, w.e, cf.t_embed_dim, m->t1.wt, m->t1.b, w.h1, D, 0, 1, 1, 0, 0, 0, c.s));
   HIP_TRY(launch_gemv(m->bf16, w.h1, D, m->t2.wt, m->t2.b, w.c, D, 0, 0, 1, 0, 0, 0, c.s));
-  const int nm = m->nmod * D;
   HIP_TRY(launch_gemv(m->bf16, w.c, D, m->mod_w, m->mod_b, w.mod, nm, 1, 0, cf.depth, (size_t)nm * D, nm, nm, c.s));
   HIP_TRY(launch_gemv(m->bf16, w.c, D, m->fmod.wt, m->fmod.b, w.fmod, 2 * D, 1, 0, 1, 0, 0, 0, c.s));
+  }
 
   // tokens
   const int text_rows = cf.attn_mode == FC_ATTN_FULL3D_CONCAT ? cf.text_len : 0;
+  {
+  ProfScope ps(c, PC_PATCH_EMBED);
   HIP_TRY(launch_patch_embed(latent, c.R, w.B, m->p_w, m->p_b, m->pos_sp, m->pos_t, w.x, cf.frames, cf.height,
                              cf.width, cf.channels, cf.patch, D, m->Ns, text_rows, c.s));
   if (text_rows)
     HIP_TRY(launch_act_to_f32_rows(m->bf16, w.y, w.x, w.B * cf.text_len, D, cf.text_len, m->Ns, 0, c.R, c.use_cfg,
                                    c.s));
+  }
 
   for (int l = 0; l < cf.depth; ++l) {
     const Block& b = m->blocks[l];
@@ -388,13 +458,17 @@ int run_step(const Ctx& c, float* latent, const fc_schedule* sched, int step, fl
   }
 
   // head: LN + modulate on the video rows, Linear D -> p*p*C, scatter back to latent layout
+  {
+  ProfScope ps(c, PC_LN_MODULATE);
   HIP_TRY(launch_ln_modulate(m->bf16, w.x, w.fmod, w.fmod + D, w.u, w.B * m->N, D, cf.ln_eps, m->Ns, m->N,
                              text_rows, c.s));
+  }
   EpiParams ep;
   ep.eps = w.eps; ep.T = cf.frames; ep.H = cf.height; ep.W = cf.width; ep.C = cf.channels; ep.p = cf.patch;
-  if ((rc = linear(c, EPI_UNPATCH, w.u, m->fout, w.B * m->N, ep)) != FC_OK) return rc;
+  if ((rc = linear(c, PC_GEMM_OTHER, EPI_UNPATCH, w.u, m->fout, w.B * m->N, ep)) != FC_OK) return rc;
 
   const size_t n = (size_t)c.R * cf.frames * cf.height * cf.width * cf.channels;
+  ProfScope ps(c, PC_CFG_DDIM);
   HIP_TRY(launch_cfg_ddim(latent, w.eps, c.use_cfg ? w.eps + n : nullptr, eps_out, n, sched->guidance_scale,
                           coef[0], coef[1], coef[2], coef[3], c.s));
   return FC_OK;
@@ -607,6 +681,32 @@ const char* fc_status_string(int status) {
 }
 
 const char* fc_last_error(void) { return g_err.c_str(); }
+
+int fc_profile_enable(fc_model* m, int32_t enable) {
+  if (!m) return fail(FC_ERR_NULL, "NULL argument");
+  m->prof.release_all();
+  m->prof.on = enable != 0;
+  return FC_OK;
+}
+
+int fc_profile_categories(void) { return PC_COUNT; }
+
+const char* fc_profile_category_name(int32_t i) { return (i >= 0 && i < PC_COUNT) ? kProfNames[i] : ""; }
+
+int fc_profile_read(fc_model* m, int32_t n, double* ms_out, int64_t* launches_out) {
+  if (!m || !ms_out || !launches_out) return fail(FC_ERR_NULL, "NULL argument");
+  if (n < PC_COUNT) return fail(FC_ERR_RANGE, "need room for fc_profile_categories() entries");
+  for (int i = 0; i < n; ++i) { ms_out[i] = 0.0; launches_out[i] = 0; }
+  for (auto& r : m->prof.recs) {
+    HIP_TRY(hipEventSynchronize(r.b));
+    float ms = 0.0f;
+    HIP_TRY(hipEventElapsedTime(&ms, r.a, r.b));
+    ms_out[r.cat] += ms;
+    launches_out[r.cat] += 1;
+  }
+  m->prof.release_all();
+  return FC_OK;
+}
 
 // ---------------------------------------------------------------- single operators
 int fc_op_linear(int32_t dtype, const void* A, const void* Wt, const float* bias, void* out, int32_t M, int32_t N,

@@ -29,6 +29,7 @@ def test_library_exports_every_declared_symbol(fc):
     # and the binding wraps each of them under the same name
     for n in names:
         assert hasattr(fc.binding, n) or n in ("fc_status_string", "fc_last_error"), n
+    assert fc.fc_profile_categories() == 14 and fc.fc_profile_category_name(8) == "attn_full3d"
 
 
 def test_schedule_coefficients_match_oracle(fc):
