@@ -178,10 +178,9 @@ int fc_op_linear_residual(int32_t dtype, const void* A, const void* Wt, const fl
                           void* hip_stream);
 
 /* Unmasked softmax(q k^T / sqrt(d)) v for G independent problems (one per
- * sequence and head).  q [G, nq, d], k [G, nk, d] (act), vt [G, d, nk_pad] (act,
- * V transposed, nk_pad = nk rounded up to 64, padding ignored), out [G, nq, d]
- * (act).  impl 0: library's choice, 1: force the plain (non-MFMA) kernel. */
-int fc_op_attention(int32_t dtype, const void* q, const void* k, const void* vt, void* out,
+ * sequence and head).  q [G, nq, d], k [G, nk, d], v [G, nk, d], out [G, nq, d]
+ * (all act).  impl 0: library's choice, 1: force the plain (non-MFMA) kernel. */
+int fc_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* out,
                     int32_t G, int32_t nq, int32_t nk, int32_t d, int32_t impl, void* hip_stream);
 
 /* out[M,D] (act) = LayerNorm(x[M,D] (f32)) * (1 + scale[D]) + shift[D]

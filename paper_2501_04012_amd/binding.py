@@ -203,8 +203,8 @@ def fc_op_linear_residual(dtype, A, Wt, bias, gate, x, M, N, K, stream=None) -> 
                                       _stream(stream)), "fc_op_linear_residual")
 
 
-def fc_op_attention(dtype, q, k, vt, out, G, nq, nk, d, impl=0, stream=None) -> None:
-    _check(_lib.fc_op_attention(dtype, _ptr(q), _ptr(k), _ptr(vt), _ptr(out), G, nq, nk, d, impl, _stream(stream)),
+def fc_op_attention(dtype, q, k, v, out, G, nq, nk, d, impl=0, stream=None) -> None:
+    _check(_lib.fc_op_attention(dtype, _ptr(q), _ptr(k), _ptr(v), _ptr(out), G, nq, nk, d, impl, _stream(stream)),
            "fc_op_attention")
 
 

@@ -5,7 +5,9 @@
 //                  (S^T = K Q^T) so that each query column lives in two lanes, the
 //                  running max / sum need one cross-lane exchange per tile, and the
 //                  probabilities are already in the register layout the P V MFMA
-//                  takes as its B operand: P never touches LDS.
+//                  takes as its B operand: P never touches LDS.  V is staged row-major
+//                  like K; the V^T fragments come from the LDS transpose read
+//                  (ds_read_b64_tr_b16), so no transposed copy of V exists anywhere.
 #include "common.h"
 
 namespace fc {
@@ -30,7 +32,7 @@ __global__ __launch_bounds__(64) void k_attn_plain(AttnParams p) {
   const int qtok = g * p.q_gstride + i * p.q_istride;
   const T* q = (const T*)p.q + (((size_t)b * p.heads + head) * p.q_tokens + qtok) * HD;
   const T* kbase = (const T*)p.k + ((size_t)kb * p.heads + head) * (size_t)p.k_tokens * HD;
-  const T* vbase = (const T*)p.vt + ((size_t)kb * p.heads + head) * (size_t)HD * p.k_tokens_pad;
+  const T* vbase = (const T*)p.v + ((size_t)kb * p.heads + head) * (size_t)p.k_tokens * HD;
 
   float qv[HD], o[HD];
 #pragma unroll
@@ -48,7 +50,7 @@ __global__ __launch_bounds__(64) void k_attn_plain(AttnParams p) {
     const float pj = exp2f(s - mn);
     l = l * alpha + pj;
 #pragma unroll
-    for (int c = 0; c < HD; ++c) o[c] = o[c] * alpha + pj * to_f32(vbase[(size_t)c * p.k_tokens_pad + ktok]);
+    for (int c = 0; c < HD; ++c) o[c] = o[c] * alpha + pj * to_f32(vbase[(size_t)ktok * HD + c]);
     m = mn;
   }
   const float inv = 1.0f / l;
@@ -82,7 +84,7 @@ static hipError_t dispatch_plain(const AttnParams& p, hipStream_t s) {
 // ---------------------------------------------------------------- flash kernel (bf16, MFMA)
 // Workgroup = 4 waves; wave w owns query rows [64w, 64w+64) of a 256-row query tile
 // (two 32-column MFMA tiles qt).  Keys are walked in tiles of 64, staged in LDS as
-// K [64][HDP] and V^T [HDV][64] (double-buffered, register-prefetched).
+// K [64][HDP] and V [64][HDV] (double-buffered, register-prefetched).
 //
 // Per key tile and wave:
 //   S^T[a][qt] (32 keys x 32 queries) = K_a (A operand) x Q_qt^T (B operand, in
@@ -90,11 +92,17 @@ static hipError_t dispatch_plain(const AttnParams& p, hipStream_t s) {
 //   Lane (i, h) of S^T holds query column i and key rows r = 8g + 4h + e.  The K row
 //   fed as MFMA row r is key perm(r) = r with bits 2 and 3 swapped, so that the 8
 //   values of registers {4(2s), .., 4(2s+1)+3} are the 8 consecutive keys
-//   16s + 8h .. + 7: exactly one 16-byte read of V^T for the P V step.
+//   16s + 8h .. + 7, the k-slice lane half h supplies in the P V step.
 //   O^T[c][qt] (32 head dims x 32 queries) += V^T_c (A operand) x P^T (B operand).
+//   A-operand lane (i, h) needs V[key 16s + 8h + x][dim 32c + i], x = 0..7: two
+//   transpose reads.  In each 16-lane group, source lane 4r + a addresses the 8
+//   bytes V[key0 + r][dim0 + 4a .. +3] and destination lane L receives
+//   V[key0 + 0..3][dim0 + L].
 //
 // HD = true head dim; HDP = HD rounded up to 16 (contraction of Q K^T); HDV = HD
 // rounded up to 32 (rows of O^T).  Pad lanes are zero-filled when staged.
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+
 template <int HD>
 struct FlashCfg {
   static constexpr int HDP = (HD + 15) / 16 * 16;
@@ -102,12 +110,11 @@ struct FlashCfg {
   static constexpr int KS = HDP / 16;        // k-steps of Q K^T
   static constexpr int CT = HDV / 32;        // O^T row tiles
   static constexpr int LDK = HDP + 8;        // LDS row of K tile (elements)
-  static constexpr int LDV = 64 + 8;         // LDS row of V^T tile
-  static constexpr int K_ELEMS = 64 * LDK, V_ELEMS = HDV * LDV;
+  static constexpr int LDV = HDV + 8;        // LDS row of V tile
+  static constexpr int K_ELEMS = 64 * LDK, V_ELEMS = 64 * LDV;
   static constexpr size_t SMEM = (size_t)2 * (K_ELEMS + V_ELEMS) * sizeof(bf16_t);
   static constexpr int CH = HD / 8;          // 16-byte chunks per K row
-  static constexpr int K_CHUNKS = 64 * CH;   // per tile
-  static constexpr int V_CHUNKS = HD * 8;    // HD rows x 8 chunks of 8 keys
+  static constexpr int CHUNKS = 64 * CH;     // per tile, K and V alike
 };
 
 template <int HD>
@@ -116,7 +123,7 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
   static_assert(HD % 8 == 0, "head dim must be a multiple of 8");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* Ks = (bf16_t*)smem_raw;                 // [2][64][LDK]
-  bf16_t* Vs = Ks + 2 * C::K_ELEMS;               // [2][HDV][LDV]
+  bf16_t* Vs = Ks + 2 * C::K_ELEMS;               // [2][64][LDV]
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int li = lane & 31, lh = lane >> 5;
@@ -133,8 +140,8 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
   const bf16_t* qbase = (const bf16_t*)p.q + ((size_t)b * p.heads + head) * (size_t)p.q_tokens * HD;
   const bf16_t* kbase = (const bf16_t*)p.k + (((size_t)kb * p.heads + head) * (size_t)p.k_tokens +
                                               (size_t)g * p.k_gstride) * HD;
-  const bf16_t* vbase = (const bf16_t*)p.vt + ((size_t)kb * p.heads + head) * (size_t)HD * p.k_tokens_pad +
-                        (size_t)g * p.k_gstride;
+  const bf16_t* vbase = (const bf16_t*)p.v + (((size_t)kb * p.heads + head) * (size_t)p.k_tokens +
+                                              (size_t)g * p.k_gstride) * HD;
 
   // ---- Q fragments: B operand, lane (i, h) holds Q[row i][16s + 8h .. +7]
   bf16x8 qf[2][C::KS];
@@ -167,34 +174,21 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
   float mrow[2] = {-INFINITY, -INFINITY};   // running max (raw scores) of this lane's query column
   float lrow[2] = {0.0f, 0.0f};             // this lane's partial sum (its 32 of the 64 keys per tile)
 
-  // ---- staging
-  constexpr int KPT = (C::K_CHUNKS + 255) / 256, VPT = (C::V_CHUNKS + 255) / 256;
-  bf16x8 rk[KPT], rv[VPT];
+  // ---- staging: K and V tiles are both [64 keys][HD] row-major, one 16-byte chunk per thread and pass
+  constexpr int CPT = (C::CHUNKS + 255) / 256;
+  bf16x8 rk[CPT], rv[CPT];
   const int nkt = (p.nk + 63) / 64;
 
   auto gload = [&](int kt) {
     const int j0 = kt * 64;
 #pragma unroll
-    for (int c = 0; c < KPT; ++c) {
+    for (int c = 0; c < CPT; ++c) {
       int ch = tid + c * 256;
-      if (ch < C::K_CHUNKS) {
+      if (ch < C::CHUNKS) {
         int row = ch / C::CH, kc = ch % C::CH;
         int j = j0 + row; j = j < p.nk ? j : p.nk - 1;          // keys past nk are masked later
         rk[c] = *(const bf16x8*)(kbase + (size_t)j * HD + kc * 8);
-      }
-    }
-#pragma unroll
-    for (int c = 0; c < VPT; ++c) {
-      int ch = tid + c * 256;
-      if (ch < C::V_CHUNKS) {
-        int row = ch / 8, jc = ch % 8;
-        int j = j0 + jc * 8;
-        bf16x8 v = *(const bf16x8*)(vbase + (size_t)row * p.k_tokens_pad + j);   // inside the padded row
-        if (j + 8 > p.nk) {                                      // padding may hold anything: zero it
-#pragma unroll
-          for (int e = 0; e < 8; ++e) if (j + e >= p.nk) v[e] = (bf16_t)0.0f;
-        }
-        rv[c] = v;
+        rv[c] = *(const bf16x8*)(vbase + (size_t)j * HD + kc * 8);
       }
     }
   };
@@ -202,34 +196,30 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
     bf16_t* ks = Ks + buf * C::K_ELEMS;
     bf16_t* vs = Vs + buf * C::V_ELEMS;
 #pragma unroll
-    for (int c = 0; c < KPT; ++c) {
+    for (int c = 0; c < CPT; ++c) {
       int ch = tid + c * 256;
-      if (ch < C::K_CHUNKS) {
+      if (ch < C::CHUNKS) {
         int row = ch / C::CH, kc = ch % C::CH;
         *(bf16x8*)(ks + row * C::LDK + kc * 8) = rk[c];
-      }
-    }
-#pragma unroll
-    for (int c = 0; c < VPT; ++c) {
-      int ch = tid + c * 256;
-      if (ch < C::V_CHUNKS) {
-        int row = ch / 8, jc = ch % 8;
-        *(bf16x8*)(vs + row * C::LDV + jc * 8) = rv[c];
+        *(bf16x8*)(vs + row * C::LDV + kc * 8) = rv[c];
       }
     }
   };
 
-  // zero the pad columns of K (head dims HD..HDP) and pad rows of V^T (HD..HDV) once, both buffers
+  // zero the pad columns once, both buffers: K head dims HD..HDP feed the contraction;
+  // V head dims HD..HDV only produce output rows that are never stored, but keep them finite
   if constexpr (C::HDP != HD) {
-    for (int i = tid; i < 2 * 64 * (C::HDP - HD); i += 256) {
-      int buf = i / (64 * (C::HDP - HD)), r = i % (64 * (C::HDP - HD));
-      Ks[buf * C::K_ELEMS + (r / (C::HDP - HD)) * C::LDK + HD + r % (C::HDP - HD)] = (bf16_t)0.0f;
+    constexpr int PW = C::HDP - HD;
+    for (int i = tid; i < 2 * 64 * PW; i += 256) {
+      int buf = i / (64 * PW), r = i % (64 * PW);
+      Ks[buf * C::K_ELEMS + (r / PW) * C::LDK + HD + r % PW] = (bf16_t)0.0f;
     }
   }
   if constexpr (C::HDV != HD) {
-    for (int i = tid; i < 2 * (C::HDV - HD) * 64; i += 256) {
-      int buf = i / ((C::HDV - HD) * 64), r = i % ((C::HDV - HD) * 64);
-      Vs[buf * C::V_ELEMS + (HD + r / 64) * C::LDV + r % 64] = (bf16_t)0.0f;
+    constexpr int PW = C::HDV - HD;
+    for (int i = tid; i < 2 * 64 * PW; i += 256) {
+      int buf = i / (64 * PW), r = i % (64 * PW);
+      Vs[buf * C::V_ELEMS + (r / PW) * C::LDV + HD + r % PW] = (bf16_t)0.0f;
     }
   }
 
@@ -238,6 +228,10 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
   __syncthreads();
 
   const int prow = (li & 0x13) | ((li & 4) << 1) | ((li & 8) >> 1);   // li with bits 2 and 3 swapped
+  // transpose-read addressing: lane 4r + a of a 16-lane group reads key row r, dims 4a..4a+3 of the
+  // group's 16 dims (lanes 16..31 and 48..63 serve dims 16..31 of the 32-dim tile)
+  const int tr_row = (lane & 15) >> 2;
+  const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
   const float cs = p.scale_log2;
 
   for (int kt = 0; kt < nkt; ++kt) {
@@ -323,8 +317,12 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
       for (int s2 = 0; s2 < 2; ++s2) {
         bf16x8 vf[C::CT];
 #pragma unroll
-        for (int c = 0; c < C::CT; ++c)
-          vf[c] = *(const bf16x8*)(vs + (c * 32 + li) * C::LDV + a * 32 + s2 * 16 + lh * 8);
+        for (int c = 0; c < C::CT; ++c) {
+          const bf16_t* src = vs + (a * 32 + s2 * 16 + lh * 8 + tr_row) * C::LDV + c * 32 + tr_col;
+          bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)src);
+          bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(src + 4 * C::LDV));
+          vf[c] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+        }
 #pragma unroll
         for (int c = 0; c < C::CT; ++c)
 #pragma unroll
@@ -379,15 +377,12 @@ static hipError_t run_flash(const AttnParams& p, hipStream_t s) {
 }
 
 // The flash kernel needs unit-stride tokens inside a group, 16-byte aligned rows
-// and group starts, and head dims it is instantiated for.
+// (head dim a multiple of 8 elements) and head dims it is instantiated for.
 static bool flash_ok(const AttnParams& p) {
   if (p.hd != 64 && p.hd != 72) return false;
   if (p.q_istride != 1 || p.k_istride != 1) return false;
   if (p.nk < 1 || p.nq < 1) return false;
-  if ((p.k_gstride % 8) != 0 || (p.k_tokens_pad % 8) != 0) return false;
-  if ((((uintptr_t)p.q | (uintptr_t)p.k | (uintptr_t)p.vt | (uintptr_t)p.out) & 15) != 0) return false;
-  // the last V^T tile read of a group must stay inside the padded row
-  if ((long long)(p.groups - 1) * p.k_gstride + (long long)((p.nk + 63) / 64) * 64 > p.k_tokens_pad) return false;
+  if ((((uintptr_t)p.q | (uintptr_t)p.k | (uintptr_t)p.v | (uintptr_t)p.out) & 15) != 0) return false;
   return true;
 }
 

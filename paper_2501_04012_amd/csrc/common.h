@@ -54,7 +54,7 @@ enum EpiMode : int {
   EPI_STORE = 0,     // out[m,n] = acc + bias
   EPI_GELU = 1,      // out[m,n] = gelu(acc + bias)
   EPI_RESID = 2,     // x[m,n] += gate[n] * (acc + bias)     (gate NULL: 1)
-  EPI_HEADS = 3,     // scatter into per-head q / k / v^T tensors
+  EPI_HEADS = 3,     // scatter into per-head q / k / v tensors
   EPI_UNPATCH = 4    // scatter token rows back into a latent-shaped fp32 tensor
 };
 
@@ -66,9 +66,9 @@ struct EpiParams {
   const float* gate = nullptr;   // EPI_RESID: [N] or NULL
   // EPI_HEADS: column n -> which = which0 + n / D (0 q, 1 k, 2 v), head = (n % D) / hd.
   // Row m -> (b, tok) = (m / tokens, m % tokens).
-  // q, k: [b, head, tok, hd];  vt: [b, head, hd, tokens_pad].
-  void* q = nullptr; void* k = nullptr; void* vt = nullptr;
-  int which0 = 0, D = 0, heads = 0, hd = 0, tokens = 0, tokens_pad = 0;
+  // q, k, v: [b, head, tok, hd].
+  void* q = nullptr; void* k = nullptr; void* v = nullptr;
+  int which0 = 0, D = 0, heads = 0, hd = 0, tokens = 0;
   // EPI_UNPATCH: row m -> (b, t, h', w'), column f -> (dh, dw, c); eps [b, T, H, W, C]
   float* eps = nullptr;
   int T = 0, H = 0, W = 0, C = 0, p = 0;
@@ -105,25 +105,13 @@ struct Epilogue {
       const int which = P.which0 + n / P.D;
       const int c = n % P.D;
       const int head = c / P.hd, dd = c % P.hd;
-      if (which < 2) {
-        T* dst = (T*)(which == 0 ? P.q : P.k);
+      T* dst = (T*)(which == 0 ? P.q : which == 1 ? P.k : P.v);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          int m = m0 + e;
-          if (m < Mvalid) {
-            int bb = m / P.tokens, tok = m % P.tokens;
-            dst[(((size_t)bb * P.heads + head) * P.tokens + tok) * P.hd + dd] = from_f32<T>(acc[e] + b);
-          }
-        }
-      } else {
-        T* dst = (T*)P.vt;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          int m = m0 + e;
-          if (m < Mvalid) {
-            int bb = m / P.tokens, tok = m % P.tokens;
-            dst[(((size_t)bb * P.heads + head) * P.hd + dd) * P.tokens_pad + tok] = from_f32<T>(acc[e] + b);
-          }
+      for (int e = 0; e < 4; ++e) {
+        int m = m0 + e;
+        if (m < Mvalid) {
+          int bb = m / P.tokens, tok = m % P.tokens;
+          dst[(((size_t)bb * P.heads + head) * P.tokens + tok) * P.hd + dd] = from_f32<T>(acc[e] + b);
         }
       }
     } else if constexpr (MODE == EPI_UNPATCH) {
@@ -148,17 +136,16 @@ struct Epilogue {
 // ---------------------------------------------------------------- attention problem description
 // One problem = one (batch row b, head, group g).  Query i of the problem is token
 // g*q_gstride + i*q_istride of batch row b; key j likewise with the k_* strides.
-//   q  [B, heads, q_tokens, hd]     k [KB, heads, k_tokens, hd]
-//   vt [KB, heads, hd, k_tokens_pad]
+//   q  [B, heads, q_tokens, hd]     k, v [KB, heads, k_tokens, hd]
 //   out[B, q_tokens, heads*hd]      (token-major, heads concatenated)
 // Keys of batch row b come from key batch kb = b < kv_split ? b : kv_split when
 // kv_shared_tail is set (guidance rows share one 'null' text), else kb = b.
 struct AttnParams {
-  const void* q; const void* k; const void* vt; void* out;
+  const void* q; const void* k; const void* v; void* out;
   int B, heads, hd;
   int groups, nq, nk;
   int q_tokens, q_gstride, q_istride;
-  int k_tokens, k_tokens_pad, k_gstride, k_istride;
+  int k_tokens, k_gstride, k_istride;
   int kv_split, kv_shared_tail;
   float scale_log2;   // softmax scale times log2(e)
 };

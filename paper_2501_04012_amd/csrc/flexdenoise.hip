@@ -217,12 +217,12 @@ void sincos_1d(double pos, int dim, float* out) {   // [sin(pos w_i) | cos(pos w
 struct Workspace {
   float *e, *h1, *c, *mod, *fmod;          // timestep path, fp32
   void *txt, *y;                           // text in act dtype, projected text
-  void *xk, *xvt;                          // cross-attention K / V^T per block (factorized)
+  void *xk, *xv;                           // cross-attention K / V per block (factorized)
   float* x;                                // residual stream fp32 [B, Ns, D]
-  void *u, *q, *k, *vt, *hid;              // activations
+  void *u, *q, *k, *v, *hid;               // activations
   float* eps;                              // [B, T, H, W, C]
   size_t bytes;
-  int B, NT, Nsp, Lp;
+  int B, NT;
 };
 
 Workspace carve(const fc_model* m, int R, int use_cfg, unsigned char* base) {
@@ -231,8 +231,6 @@ Workspace carve(const fc_model* m, int R, int use_cfg, unsigned char* base) {
   Workspace w{};
   w.B = R * (use_cfg ? 2 : 1);
   w.NT = R + (use_cfg ? 1 : 0);                 // distinct texts: R prompts (+ the shared null)
-  w.Nsp = (int)round_up(m->Ns, 64);
-  w.Lp = (int)round_up(c.text_len, 64);
   const size_t rows = (size_t)w.B * m->Ns;
   Carver cv(base);
   w.e = (float*)cv.take((size_t)c.t_embed_dim * 4);
@@ -244,13 +242,13 @@ Workspace carve(const fc_model* m, int R, int use_cfg, unsigned char* base) {
   w.y = cv.take((size_t)w.NT * c.text_len * D * es);
   if (c.attn_mode == FC_ATTN_FACTORIZED_CROSS) {
     w.xk = cv.take((size_t)c.depth * w.NT * c.text_len * D * es);
-    w.xvt = cv.take((size_t)c.depth * w.NT * w.Lp * D * es);
+    w.xv = cv.take((size_t)c.depth * w.NT * c.text_len * D * es);
   }
   w.x = (float*)cv.take(rows * D * 4);
   w.u = cv.take(rows * D * es);
   w.q = cv.take(rows * D * es);
   w.k = cv.take(rows * D * es);
-  w.vt = cv.take((size_t)w.B * D * w.Nsp * es);
+  w.v = cv.take(rows * D * es);
   w.hid = cv.take(rows * c.mlp_dim * es);
   w.eps = (float*)cv.take((size_t)w.B * c.frames * c.height * c.width * c.channels * 4);
   w.bytes = cv.off;
@@ -291,12 +289,12 @@ int linear(const Ctx& c, int cat, int mode, const void* A, const Linear& L, int 
   return FC_OK;
 }
 
-EpiParams heads_epi(const Ctx& c, void* q, void* k, void* vt, int which0, int tokens, int tokens_pad) {
+EpiParams heads_epi(const Ctx& c, void* q, void* k, void* v, int which0, int tokens) {
   EpiParams ep;
-  ep.q = q; ep.k = k; ep.vt = vt;
+  ep.q = q; ep.k = k; ep.v = v;
   ep.which0 = which0;
   ep.D = c.m->cfg.hidden; ep.heads = c.m->cfg.heads; ep.hd = c.m->hd;
-  ep.tokens = tokens; ep.tokens_pad = tokens_pad;
+  ep.tokens = tokens;
   return ep;
 }
 
@@ -320,9 +318,9 @@ int prepare(const Ctx& c, const float* cond, const float* null_cond) {
   if (cf.attn_mode == FC_ATTN_FACTORIZED_CROSS) {
     for (int l = 0; l < cf.depth; ++l) {
       void* xk = (unsigned char*)w.xk + (size_t)l * w.NT * cf.text_len * cf.hidden * m->esz;
-      void* xvt = (unsigned char*)w.xvt + (size_t)l * w.NT * w.Lp * cf.hidden * m->esz;
+      void* xv = (unsigned char*)w.xv + (size_t)l * w.NT * cf.text_len * cf.hidden * m->esz;
       rc = linear(c, PC_GEMM_OTHER, EPI_HEADS, w.y, m->blocks[l].xkv, w.NT * cf.text_len,
-                  heads_epi(c, nullptr, xk, xvt, 1, cf.text_len, w.Lp));
+                  heads_epi(c, nullptr, xk, xv, 1, cf.text_len));
       if (rc != FC_OK) return rc;
     }
   }
@@ -343,12 +341,12 @@ int self_attention_branch(const Ctx& c, const Linear& qkv, const Linear& proj, c
   const fc_model_config& cf = m->cfg;
   const Workspace& w = c.w;
   const int rows = w.B * m->Ns;
-  int rc = linear(c, PC_GEMM_QKV, EPI_HEADS, w.u, qkv, rows, heads_epi(c, w.q, w.k, w.vt, 0, m->Ns, w.Nsp));
+  int rc = linear(c, PC_GEMM_QKV, EPI_HEADS, w.u, qkv, rows, heads_epi(c, w.q, w.k, w.v, 0, m->Ns));
   if (rc != FC_OK) return rc;
   AttnParams ap{};
-  ap.q = w.q; ap.k = w.k; ap.vt = w.vt; ap.out = w.u;
+  ap.q = w.q; ap.k = w.k; ap.v = w.v; ap.out = w.u;
   ap.B = w.B; ap.heads = cf.heads; ap.hd = m->hd;
-  ap.q_tokens = ap.k_tokens = m->Ns; ap.k_tokens_pad = w.Nsp;
+  ap.q_tokens = ap.k_tokens = m->Ns;
   if (mode == 0) { ap.groups = cf.frames; ap.nq = ap.nk = m->S; ap.q_gstride = ap.k_gstride = m->S; ap.q_istride = ap.k_istride = 1; }
   else if (mode == 1) { ap.groups = m->S; ap.nq = ap.nk = cf.frames; ap.q_gstride = ap.k_gstride = 1; ap.q_istride = ap.k_istride = m->S; }
   else { ap.groups = 1; ap.nq = ap.nk = m->Ns; ap.q_gstride = ap.k_gstride = 0; ap.q_istride = ap.k_istride = 1; }
@@ -370,17 +368,17 @@ int cross_attention_branch(const Ctx& c, const Block& b, int layer) {
   const int rows = w.B * m->Ns;
   int rc = ln_mod(c, nullptr, nullptr);
   if (rc != FC_OK) return rc;
-  rc = linear(c, PC_GEMM_PROJ, EPI_HEADS, w.u, b.xq, rows, heads_epi(c, w.q, nullptr, nullptr, 0, m->Ns, w.Nsp));
+  rc = linear(c, PC_GEMM_PROJ, EPI_HEADS, w.u, b.xq, rows, heads_epi(c, w.q, nullptr, nullptr, 0, m->Ns));
   if (rc != FC_OK) return rc;
   AttnParams ap{};
   ap.q = w.q;
   ap.k = (unsigned char*)w.xk + (size_t)layer * w.NT * cf.text_len * cf.hidden * m->esz;
-  ap.vt = (unsigned char*)w.xvt + (size_t)layer * w.NT * w.Lp * cf.hidden * m->esz;
+  ap.v = (unsigned char*)w.xv + (size_t)layer * w.NT * cf.text_len * cf.hidden * m->esz;
   ap.out = w.u;
   ap.B = w.B; ap.heads = cf.heads; ap.hd = m->hd;
   ap.groups = 1; ap.nq = m->Ns; ap.nk = cf.text_len;
   ap.q_tokens = m->Ns; ap.q_gstride = 0; ap.q_istride = 1;
-  ap.k_tokens = cf.text_len; ap.k_tokens_pad = w.Lp; ap.k_gstride = 0; ap.k_istride = 1;
+  ap.k_tokens = cf.text_len; ap.k_gstride = 0; ap.k_istride = 1;
   ap.kv_split = c.R; ap.kv_shared_tail = c.use_cfg;      // guidance rows all read the null text
   ap.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)m->hd));
   {
@@ -729,16 +727,16 @@ int fc_op_linear_residual(int32_t dtype, const void* A, const void* Wt, const fl
   return FC_OK;
 }
 
-int fc_op_attention(int32_t dtype, const void* q, const void* k, const void* vt, void* out, int32_t G, int32_t nq,
+int fc_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* out, int32_t G, int32_t nq,
                     int32_t nk, int32_t d, int32_t impl, void* stream) {
-  if (!q || !k || !vt || !out) return fail(FC_ERR_NULL, "NULL argument");
+  if (!q || !k || !v || !out) return fail(FC_ERR_NULL, "NULL argument");
   if (G < 0 || nq < 0 || nk < 1 || d < 1) return fail(FC_ERR_RANGE, "bad size");
   AttnParams ap{};
-  ap.q = q; ap.k = k; ap.vt = vt; ap.out = out;
+  ap.q = q; ap.k = k; ap.v = v; ap.out = out;
   ap.B = G; ap.heads = 1; ap.hd = d;
   ap.groups = 1; ap.nq = nq; ap.nk = nk;
   ap.q_tokens = nq; ap.q_gstride = 0; ap.q_istride = 1;
-  ap.k_tokens = nk; ap.k_tokens_pad = (int)round_up(nk, 64); ap.k_gstride = 0; ap.k_istride = 1;
+  ap.k_tokens = nk; ap.k_gstride = 0; ap.k_istride = 1;
   ap.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)d));
   hipError_t e = launch_attention(dtype == FC_BF16, ap, impl, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return fail(FC_ERR_UNSUPPORTED, "head dim not supported");

@@ -93,12 +93,9 @@ def _attn_case(fc, G, nq, nk, d, gain, bf, impl):
     q, k, v = np.stack(qs), np.stack(ks), np.stack(vs)
     if bf:
         q, k, v = BF(q), BF(k), BF(v)
-    nkp = (nk + 63) // 64 * 64
-    vt = np.full((G, d, nkp), np.nan, dtype=np.float32)       # poison the padding: it must be ignored
-    vt[:, :, :nk] = v.transpose(0, 2, 1)
     want = dit.attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64))
     out = torch.full((G, nq, d), float("nan"), dtype=torch.bfloat16 if bf else torch.float32, device="cuda:0")
-    fc.fc_op_attention(fc.FC_BF16 if bf else fc.FC_F32, dev(q, bf), dev(k, bf), dev(vt, bf), out, G, nq, nk, d, impl)
+    fc.fc_op_attention(fc.FC_BF16 if bf else fc.FC_F32, dev(q, bf), dev(k, bf), dev(v, bf), out, G, nq, nk, d, impl)
     torch.cuda.synchronize()
     return host(out), want
 
@@ -127,9 +124,9 @@ def test_attention_rows_are_convex_combinations(fc):
     G, nq, nk, d = 2, 130, 1000, 64
     q, k, _ = synth.sharp_qkv(3, nq, nk, d, gain=2.0)
     q, k = np.stack([BF(q)] * G), np.stack([BF(k)] * G)
-    vt = np.ones((G, d, 1024), dtype=np.float32)
+    v = np.ones((G, nk, d), dtype=np.float32)
     out = torch.empty((G, nq, d), dtype=torch.bfloat16, device="cuda:0")
-    fc.fc_op_attention(fc.FC_BF16, dev(q, True), dev(k, True), dev(vt, True), out, G, nq, nk, d, 0)
+    fc.fc_op_attention(fc.FC_BF16, dev(q, True), dev(k, True), dev(v, True), out, G, nq, nk, d, 0)
     torch.cuda.synchronize()
     np.testing.assert_allclose(host(out), 1.0, atol=8e-3)
 
