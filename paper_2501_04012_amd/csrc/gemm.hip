@@ -8,25 +8,175 @@
 
 namespace fc {
 
-// ---------------------------------------------------------------- bf16 MFMA kernel
-// Block tile BM x BN x BK, 4 waves arranged WR x WC, each wave owns a
-// (BM/WR) x (BN/WC) tile built from 32x32 MFMA accumulators.
+// ---------------------------------------------------------------- bf16 MFMA kernel, direct-to-LDS
+// Same tiling and MFMA layout as k_gemm_bf16 below, but the operand tiles go from
+// global memory straight into LDS (global_load_lds_dwordx4: lane l's 16 bytes land at
+// base + 16 l), S stages deep, with no register staging and no ds_write.
+//
+// LDS layout of a stage: BM rows of A then BN rows of B, BK*2 bytes each, unpadded.
+// A 256-byte LDS line holds RPL = 128/BK rows; chunk kc (16 bytes) of row r sits at
+//   line r/RPL, slot (r % RPL) * CPR + (kc ^ ((r/RPL) % CPR)),   CPR = BK/8,
+// so that the 16 rows a ds_read_b128 touches at one kc fall into 16 distinct slots
+// (no bank conflicts).  Because the DMA fixes the LDS position per lane, the swizzle
+// is applied on the global side: each lane fetches the chunk that belongs in its slot.
+//
+// Pipeline per K tile: wait until this tile's loads have landed (vmcnt), barrier
+// (publishes every wave's part and frees the stage read in the previous iteration),
+// issue the loads of tile kt+S-1 into that stage, then run the MFMAs of tile kt.
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void gbl_void;
+
+// s_waitcnt vmcnt(N) only (gfx9 encoding: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt_hi[15:14])
+template <int N> __device__ __forceinline__ void wait_vm() {
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+template <int BM, int BN, int BK, int WR, int WC, int S, typename Epi>
+__global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __restrict__ A,
+                                                            const bf16_t* __restrict__ Wt, int M, int N, int K,
+                                                            int tiles_m, int tiles_n, Epi epi) {
+  constexpr int NW = WR * WC;
+  constexpr int WTM = BM / WR, WTN = BN / WC;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  constexpr int CPR = BK / 8;              // 16-byte chunks per row
+  constexpr int RPL = 16 / CPR;            // rows per 256-byte LDS line
+  constexpr int RW = 4 * RPL;              // rows per wave-load (1 KB)
+  constexpr int ROWS = BM + BN;
+  constexpr int WL = ROWS / RW;            // wave-loads per stage
+  constexpr int LPW = WL / NW;             // per wave
+  constexpr int STAGE_BYTES = ROWS * BK * 2;
+  static_assert(WL % NW == 0, "loads must divide among waves");
+  static_assert(BM % RW == 0, "A/B boundary must fall between wave-loads");
+
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave / WC, wc = wave % WC;
+  const int li = lane & 31, lh = lane >> 5;
+
+  const int total = tiles_m * tiles_n;
+  const int bid = blockIdx.x;
+  const int xcd = bid & 7, local = bid >> 3;
+  const int t = ((local >> 5) * 8 + xcd) * 32 + (local & 31);
+  if (t >= total) return;
+  constexpr int GM = 8;
+  const int per_group = GM * tiles_n;
+  const int group = t / per_group;
+  const int first_m = group * GM;
+  const int gsz = min(tiles_m - first_m, GM);
+  const int tm = first_m + (t % per_group) % gsz;
+  const int tn = (t % per_group) / gsz;
+  const int bm0 = tm * BM, bn0 = tn * BN;
+
+  // ---- global source pointers of this lane for its LPW wave-loads
+  const bf16_t* gp[LPW];
+#pragma unroll
+  for (int j = 0; j < LPW; ++j) {
+    const int wl = wave + NW * j;
+    const int line_in = lane >> 4, slot = lane & 15;
+    const int row = wl * RW + line_in * RPL + slot / CPR;
+    const int kc = (slot % CPR) ^ ((wl * 4 + line_in) % CPR);
+    if (row < BM) {
+      int gm = bm0 + row; gm = gm < M ? gm : M - 1;
+      gp[j] = A + (size_t)gm * K + kc * 8;
+    } else {
+      int gn = bn0 + row - BM; gn = gn < N ? gn : N - 1;
+      gp[j] = Wt + (size_t)gn * K + kc * 8;
+    }
+  }
+  auto issue = [&](int kt, int stage) {
+#pragma unroll
+    for (int j = 0; j < LPW; ++j) {
+      const int wl = wave + NW * j;
+      __builtin_amdgcn_global_load_lds((gbl_void*)(gp[j] + (size_t)kt * BK),
+                                       (lds_void*)(smem + stage * STAGE_BYTES + wl * 1024), 16, 0, 0);
+    }
+  };
+
+  // ---- fragment read offsets (bytes within a stage)
+  const int ra = wr * WTM + li, rb = BM + wc * WTN + li;
+  const int a_row = (ra / RPL) * 256 + (ra % RPL) * CPR * 16, a_x = (ra / RPL) % CPR;
+  const int b_row = (rb / RPL) * 256 + (rb % RPL) * CPR * 16, b_x = (rb / RPL) % CPR;
+  constexpr int TILE_STRIDE = (32 / RPL) * 256;   // 32 rows further down
+
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  const int nkt = K / BK;
+#pragma unroll
+  for (int p = 0; p < S - 1; ++p)
+    if (p < nkt) issue(p, p);
+
+  for (int kt = 0; kt < nkt; ++kt) {
+    if (kt + S - 2 < nkt) wait_vm<LPW * (S - 2)>(); else wait_vm<0>();
+    __builtin_amdgcn_s_barrier();
+    if (kt + S - 1 < nkt) issue(kt + S - 1, (kt + S - 1) % S);
+    const unsigned char* st = smem + (kt % S) * STAGE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 fa[TM], fb[TN];
+      const unsigned char* pa = st + a_row + (((2 * ks + lh) ^ a_x) << 4);
+      const unsigned char* pb = st + b_row + (((2 * ks + lh) ^ b_x) << 4);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8*)(pa + i * TILE_STRIDE);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) fb[j] = *(const bf16x8*)(pb + j * TILE_STRIDE);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+  }
+
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = bn0 + wc * WTN + j * 32 + li;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int m0 = bm0 + wr * WTM + i * 32 + g * 8 + lh * 4;
+        float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+        epi.store4(m0, n, v);
+      }
+    }
+}
+
+// ---------------------------------------------------------------- bf16 MFMA kernel, register-staged
+// Block tile BM x BN x BK, NW = WR x WC waves, each wave owns a (BM/WR) x (BN/WC)
+// tile built from 32x32 MFMA accumulators.
 //
 // MFMA operand layout (32x32x16, wave64), lane = i + 32*h:
 //   A: row i of the 32-row tile, k = 8h .. 8h+7        (8 bf16 = one 16-byte LDS read)
 //   B: column i of the 32-col tile, k = 8h .. 8h+7
 //   D: column i, rows 8g + 4h + e for register 4g + e   (g, e in 0..3)
 // Global -> register -> LDS staging, double-buffered LDS: the loads of tile kt+1
-// are issued before the MFMAs of tile kt and written to the other buffer after.
+// are issued before the MFMAs of tile kt and written to the other buffer after,
+// one barrier per K tile.
+//
+// Tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its
+// own L2, and an XCD runs 32 workgroups at a time.  Id -> tile index is chosen so
+// that the 32 concurrent workgroups of one XCD hold 32 consecutive tile indices,
+// and consecutive indices walk GM = 8 tile rows before moving to the next tile
+// column: an XCD works on an 8 x 4 patch of C and streams 8 + 4 operand panels
+// through its L2 instead of 1 + 32.
 template <int BM, int BN, int BK, int WR, int WC, typename Epi>
-__global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A, const bf16_t* __restrict__ Wt,
-                                                   int M, int N, int K, Epi epi) {
+__global__ __launch_bounds__(WR * WC * 64) void k_gemm_bf16(const bf16_t* __restrict__ A,
+                                                            const bf16_t* __restrict__ Wt, int M, int N, int K,
+                                                            int tiles_m, int tiles_n, Epi epi) {
+  constexpr int NT = WR * WC * 64;            // threads
   constexpr int LDT = BK + 8;                 // padded LDS row (elements)
   constexpr int WTM = BM / WR, WTN = BN / WC; // wave tile
   constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int CPR = BK / 8;                 // 16-byte chunks per tile row
-  constexpr int A_CHUNKS = BM * CPR / 256, B_CHUNKS = BN * CPR / 256;
-  static_assert(WR * WC == 4 && BM * CPR % 256 == 0 && BN * CPR % 256 == 0, "tile/threads mismatch");
+  constexpr int A_CHUNKS = BM * CPR / NT, B_CHUNKS = BN * CPR / NT;
+  static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/threads mismatch");
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   bf16_t* As = (bf16_t*)smem_raw;                        // [2][BM][LDT]
@@ -36,18 +186,20 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
   const int wr = wave / WC, wc = wave % WC;
   const int li = lane & 31, lh = lane >> 5;
 
-  // XCD-aware tile order: consecutive workgroups go to different XCDs (8 of them),
-  // so give each XCD a contiguous band of tiles that shares A rows in its own L2.
-  const int tiles_n = gridDim.x, tiles_m = gridDim.y;
+  // workgroup id -> tile
   const int total = tiles_m * tiles_n;
-  int bid = blockIdx.y * tiles_n + blockIdx.x;
-  {
-    const int per = (total + 7) / 8;
-    int xcd = bid % 8, idx = bid / 8;
-    int remapped = xcd * per + idx;
-    if ((total % 8) == 0) bid = remapped;   // exact split only; otherwise keep the natural order
-  }
-  const int bm0 = (bid / tiles_n) * BM, bn0 = (bid % tiles_n) * BN;
+  const int bid = blockIdx.x;
+  const int xcd = bid & 7, local = bid >> 3;
+  const int t = ((local >> 5) * 8 + xcd) * 32 + (local & 31);
+  if (t >= total) return;
+  constexpr int GM = 8;
+  const int per_group = GM * tiles_n;
+  const int group = t / per_group;
+  const int first_m = group * GM;
+  const int gsz = min(tiles_m - first_m, GM);
+  const int tm = first_m + (t % per_group) % gsz;
+  const int tn = (t % per_group) / gsz;
+  const int bm0 = tm * BM, bn0 = tn * BN;
 
   f32x16 acc[TM][TN];
 #pragma unroll
@@ -60,31 +212,38 @@ __global__ __launch_bounds__(256) void k_gemm_bf16(const bf16_t* __restrict__ A,
   bf16x8 ra[A_CHUNKS], rb[B_CHUNKS];
   const int nkt = K / BK;
 
+  // per-thread source rows (clamped: rows past M / N are loaded but never stored)
+  const bf16_t* ga[A_CHUNKS];
+  const bf16_t* gb[B_CHUNKS];
+#pragma unroll
+  for (int c = 0; c < A_CHUNKS; ++c) {
+    int ch = tid + c * NT, row = ch / CPR, kc = ch % CPR;
+    int gm = bm0 + row; gm = gm < M ? gm : M - 1;
+    ga[c] = A + (size_t)gm * K + kc * 8;
+  }
+#pragma unroll
+  for (int c = 0; c < B_CHUNKS; ++c) {
+    int ch = tid + c * NT, row = ch / CPR, kc = ch % CPR;
+    int gn = bn0 + row; gn = gn < N ? gn : N - 1;
+    gb[c] = Wt + (size_t)gn * K + kc * 8;
+  }
   auto gload = [&](int kt) {
 #pragma unroll
-    for (int c = 0; c < A_CHUNKS; ++c) {
-      int ch = tid + c * 256, row = ch / CPR, kc = ch % CPR;
-      int gm = bm0 + row; gm = gm < M ? gm : M - 1;          // clamp: rows past M are never stored
-      ra[c] = *(const bf16x8*)(A + (size_t)gm * K + (size_t)kt * BK + kc * 8);
-    }
+    for (int c = 0; c < A_CHUNKS; ++c) ra[c] = *(const bf16x8*)(ga[c] + (size_t)kt * BK);
 #pragma unroll
-    for (int c = 0; c < B_CHUNKS; ++c) {
-      int ch = tid + c * 256, row = ch / CPR, kc = ch % CPR;
-      int gn = bn0 + row; gn = gn < N ? gn : N - 1;
-      rb[c] = *(const bf16x8*)(Wt + (size_t)gn * K + (size_t)kt * BK + kc * 8);
-    }
+    for (int c = 0; c < B_CHUNKS; ++c) rb[c] = *(const bf16x8*)(gb[c] + (size_t)kt * BK);
   };
   auto sstore = [&](int buf) {
     bf16_t* a = As + buf * BM * LDT;
     bf16_t* b = Bs + buf * BN * LDT;
 #pragma unroll
     for (int c = 0; c < A_CHUNKS; ++c) {
-      int ch = tid + c * 256, row = ch / CPR, kc = ch % CPR;
+      int ch = tid + c * NT, row = ch / CPR, kc = ch % CPR;
       *(bf16x8*)(a + row * LDT + kc * 8) = ra[c];
     }
 #pragma unroll
     for (int c = 0; c < B_CHUNKS; ++c) {
-      int ch = tid + c * 256, row = ch / CPR, kc = ch % CPR;
+      int ch = tid + c * NT, row = ch / CPR, kc = ch % CPR;
       *(bf16x8*)(b + row * LDT + kc * 8) = rb[c];
     }
   };
@@ -182,8 +341,29 @@ static hipError_t run_mfma(const void* A, const void* Wt, int M, int N, int K, c
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  dim3 grid(ceil_div(N, BN), ceil_div(M, BM));
-  kern<<<grid, 256, smem, s>>>((const bf16_t*)A, (const bf16_t*)Wt, M, N, K, epi);
+  const int tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
+  const long long total = (long long)tiles_m * tiles_n;
+  const unsigned grid = (unsigned)((total + 255) / 256 * 256);   // whole rounds of 8 XCDs x 32 workgroups
+  kern<<<grid, WR * WC * 64, smem, s>>>((const bf16_t*)A, (const bf16_t*)Wt, M, N, K, tiles_m, tiles_n, epi);
+  return hipGetLastError();
+}
+
+template <int BM, int BN, int BK, int WR, int WC, int S, int MODE>
+static hipError_t run_dlds(const void* A, const void* Wt, int M, int N, int K, const EpiParams& ep, hipStream_t s) {
+  using Epi = Epilogue<bf16_t, MODE>;
+  Epi epi{ep, M, N};
+  constexpr size_t smem = (size_t)S * (BM + BN) * BK * sizeof(bf16_t);
+  auto kern = k_gemm_dlds<BM, BN, BK, WR, WC, S, Epi>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  const int tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
+  const long long total = (long long)tiles_m * tiles_n;
+  const unsigned grid = (unsigned)((total + 255) / 256 * 256);
+  kern<<<grid, WR * WC * 64, smem, s>>>((const bf16_t*)A, (const bf16_t*)Wt, M, N, K, tiles_m, tiles_n, epi);
   return hipGetLastError();
 }
 
@@ -203,8 +383,8 @@ static hipError_t dispatch_mode(int bf16, const void* A, const void* Wt, int M, 
   const bool aligned = (((uintptr_t)A | (uintptr_t)Wt) & 15) == 0;
   if (K % 64 != 0 || !aligned || N < 32) return run_plain<bf16_t, MODE>(A, Wt, M, N, K, ep, s);
   // tile choice: the big tile when it still gives every CU work, else the small one
-  const long long big_tiles = (long long)ceil_div(M, 256) * ceil_div(N, 128);
-  if (big_tiles >= 512) return run_mfma<256, 128, 64, 2, 2, MODE>(A, Wt, M, N, K, ep, s);
+  const long long big_tiles = (long long)ceil_div(M, 256) * ceil_div(N, 256);
+  if (big_tiles >= 512) return run_dlds<256, 256, 64, 4, 2, 2, MODE>(A, Wt, M, N, K, ep, s);
   return run_mfma<128, 128, 64, 2, 2, MODE>(A, Wt, M, N, K, ep, s);
 }
 
