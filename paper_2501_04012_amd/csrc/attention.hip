@@ -10,6 +10,8 @@
 //                  (ds_read_b64_tr_b16), so no transposed copy of V exists anywhere.
 #include "common.h"
 
+#include <type_traits>
+
 namespace fc {
 
 __device__ __forceinline__ int key_batch(const AttnParams& p, int b) {
@@ -94,6 +96,8 @@ static hipError_t dispatch_plain(const AttnParams& p, hipStream_t s) {
 //   values of registers {4(2s), .., 4(2s+1)+3} are the 8 consecutive keys
 //   16s + 8h .. + 7, the k-slice lane half h supplies in the P V step.
 //   O^T[c][qt] (32 head dims x 32 queries) += V^T_c (A operand) x P^T (B operand).
+//   Softmax cost per score is one max3 half, one exp2, half a cvt_pk and half a dot2:
+//   the subtraction of the running reference rides in the MFMA accumulator.
 //   A-operand lane (i, h) needs V[key 16s + 8h + x][dim 32c + i], x = 0..7: two
 //   transpose reads.  In each 16-lane group, source lane 4r + a addresses the 8
 //   bytes V[key0 + r][dim0 + 4a .. +3] and destination lane L receives
@@ -102,6 +106,7 @@ static hipError_t dispatch_plain(const AttnParams& p, hipStream_t s) {
 // HD = true head dim; HDP = HD rounded up to 16 (contraction of Q K^T); HDV = HD
 // rounded up to 32 (rows of O^T).  Pad lanes are zero-filled when staged.
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 template <int HD>
 struct FlashCfg {
@@ -160,6 +165,10 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
 #pragma unroll
         for (int e = 0; e < 8; ++e) v[e] = (bf16_t)0.0f;
       }
+      if (p.scale_log2 != 1.0f) {            // queries not pre-multiplied by scale*log2(e): do it here
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = (bf16_t)((float)v[e] * p.scale_log2);
+      }
       qf[qt][s] = v;
     }
   }
@@ -171,7 +180,6 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
     for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[c][qt][r] = 0.0f;
-  float mrow[2] = {-INFINITY, -INFINITY};   // running max (raw scores) of this lane's query column
   float lrow[2] = {0.0f, 0.0f};             // this lane's partial sum (its 32 of the 64 keys per tile)
 
   // ---- staging: K and V tiles are both [64 keys][HD] row-major, one 16-byte chunk per thread and pass
@@ -232,22 +240,28 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
   // group's 16 dims (lanes 16..31 and 48..63 serve dims 16..31 of the 32-dim tile)
   const int tr_row = (lane & 15) >> 2;
   const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-  const float cs = p.scale_log2;
 
-  for (int kt = 0; kt < nkt; ++kt) {
+  // minus the running reference of each query column, splat over an accumulator: it is the C
+  // operand of the first score MFMA of every tile, so no per-tile accumulator initialisation
+  f32x16 negm[2];
+#pragma unroll
+  for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) negm[qt][r] = 0.0f;
+  bf16x2 ones;
+  ones[0] = (bf16_t)1.0f; ones[1] = (bf16_t)1.0f;
+  constexpr float kLazy = 8.0f;
+
+  // One key tile.  MASKED: the tile holds keys past nk (only the last tile can).
+  auto tile = [&](int kt, auto masked_tag) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
     const int buf = kt & 1;
     if (kt + 1 < nkt) gload(kt + 1);
     const bf16_t* ks = Ks + buf * C::K_ELEMS;
     const bf16_t* vs = Vs + buf * C::V_ELEMS;
 
-    // ---- S^T = K Q^T
+    // ---- S^T = K Q^T - m (Q carries the factor scale*log2(e))
     f32x16 sacc[2][2];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-      for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) sacc[a][qt][r] = 0.0f;
 #pragma unroll
     for (int s = 0; s < C::KS; ++s) {
       bf16x8 kf[2];
@@ -257,12 +271,12 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
       for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt)
-          sacc[a][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[a], qf[qt][s], sacc[a][qt], 0, 0, 0);
+          sacc[a][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[a], qf[qt][s], s == 0 ? negm[qt] : sacc[a][qt],
+                                                                0, 0, 0);
     }
 
-    // ---- mask keys past nk (last tile only).  Register 4g+e of tile a is key
-    //      32a + 16(g/2) + 8h + 4(g%2) + e of this tile.
-    if (kt == nkt - 1 && (p.nk & 63) != 0) {
+    // ---- mask keys past nk.  Register 4g+e of tile a is key 32a + 16(g/2) + 8h + 4(g%2) + e.
+    if constexpr (MASKED) {
       const int rem = p.nk - kt * 64;
 #pragma unroll
       for (int a = 0; a < 2; ++a)
@@ -275,39 +289,64 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
           }
     }
 
-    // ---- online softmax per query column, P packed to bf16 in B-operand order
-    bf16x8 pf[2][2][2];       // [qt][a][s2]
+    // ---- lazy reference update.  mx = (tile max) - m per query column.  Exponents up to
+    //      kLazy are let through (p <= 2^kLazy, harmless in fp32/bf16); only when a column
+    //      exceeds it, or on the first tile, is m moved and O, l, S rescaled.  The branch is
+    //      wave-uniform and rare after the first tiles.
+    float mx[2];
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
-      float mx = sacc[0][qt][0];
+      float v = sacc[0][qt][0];
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[a][qt][r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float mn = fmaxf(mrow[qt], mx);          // finite: every tile has at least one valid key
-      const float alpha = __builtin_amdgcn_exp2f((mrow[qt] - mn) * cs);
-      mrow[qt] = mn;
-      const float mc = mn * cs;
-      float sum = 0.0f;
+        for (int r = 0; r < 16; ++r) v = fmaxf(v, sacc[a][qt][r]);
+      mx[qt] = fmaxf(v, __shfl_xor(v, 32, 64));     // finite: every tile has at least one valid key
+    }
+    const bool first = kt == 0;
+    if (__builtin_expect(__any(first || mx[0] > kLazy || mx[1] > kLazy), 0)) {
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        const float delta = (first || mx[qt] > kLazy) ? mx[qt] : 0.0f;
+        // on the first tile O and l are zero and exp2(-delta) may overflow: scale by 0 instead
+        const float alpha = first ? 0.0f : __builtin_amdgcn_exp2f(-delta);
+        lrow[qt] *= alpha;
+#pragma unroll
+        for (int c = 0; c < C::CT; ++c)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[c][qt][r] *= alpha;
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sacc[a][qt][r] -= delta;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) negm[qt][r] -= delta;
+      }
+    }
+
+    // ---- P = exp2(S), packed to bf16 in B-operand order; the row sum adds the rounded
+    //      values (dot2 with ones), i.e. exactly what multiplies V.
+    bf16x8 pf[2][2][2];       // [qt][a][s2]
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+      float sum = lrow[qt];
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          bf16x8 pk;
+          u32x4 pw;
 #pragma unroll
-          for (int x = 0; x < 8; ++x) {
-            float pv = __builtin_amdgcn_exp2f(sacc[a][qt][8 * s2 + x] * cs - mc);
-            sum += pv;
-            pk[x] = (bf16_t)pv;
+          for (int x = 0; x < 4; ++x) {
+            bf16x2 pp;
+            pp[0] = (bf16_t)__builtin_amdgcn_exp2f(sacc[a][qt][8 * s2 + 2 * x]);
+            pp[1] = (bf16_t)__builtin_amdgcn_exp2f(sacc[a][qt][8 * s2 + 2 * x + 1]);
+            sum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, sum, false);
+            pw[x] = __builtin_bit_cast(unsigned int, pp);
           }
+          const bf16x8 pk = __builtin_bit_cast(bf16x8, pw);
           pf[qt][a][s2] = pk;
         }
-      lrow[qt] = lrow[qt] * alpha + sum;
-#pragma unroll
-      for (int c = 0; c < C::CT; ++c)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[c][qt][r] *= alpha;
+      lrow[qt] = sum;
     }
 
     // ---- O^T += V^T P^T
@@ -332,7 +371,11 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
 
     if (kt + 1 < nkt) sstore(buf ^ 1);
     __syncthreads();
-  }
+  };
+
+  const int nfull = p.nk / 64;
+  for (int kt = 0; kt < nfull; ++kt) tile(kt, std::false_type{});
+  if (nfull < nkt) tile(nfull, std::true_type{});
 
   // ---- finish: O / l, write token-major.  Lane (i, h) holds query column i, head
   //      dims 32c + 8g + 4h + e in register 4g + e.

@@ -67,8 +67,10 @@ struct EpiParams {
   // EPI_HEADS: column n -> which = which0 + n / D (0 q, 1 k, 2 v), head = (n % D) / hd.
   // Row m -> (b, tok) = (m / tokens, m % tokens).
   // q, k, v: [b, head, tok, hd].
+  // Queries are stored multiplied by qscale (softmax scale * log2 e), in fp32 before rounding.
   void* q = nullptr; void* k = nullptr; void* v = nullptr;
   int which0 = 0, D = 0, heads = 0, hd = 0, tokens = 0;
+  float qscale = 1.0f;
   // EPI_UNPATCH: row m -> (b, t, h', w'), column f -> (dh, dw, c); eps [b, T, H, W, C]
   float* eps = nullptr;
   int T = 0, H = 0, W = 0, C = 0, p = 0;
@@ -106,12 +108,13 @@ struct Epilogue {
       const int c = n % P.D;
       const int head = c / P.hd, dd = c % P.hd;
       T* dst = (T*)(which == 0 ? P.q : which == 1 ? P.k : P.v);
+      const float sc = which == 0 ? P.qscale : 1.0f;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         int m = m0 + e;
         if (m < Mvalid) {
           int bb = m / P.tokens, tok = m % P.tokens;
-          dst[(((size_t)bb * P.heads + head) * P.tokens + tok) * P.hd + dd] = from_f32<T>(acc[e] + b);
+          dst[(((size_t)bb * P.heads + head) * P.tokens + tok) * P.hd + dd] = from_f32<T>((acc[e] + b) * sc);
         }
       }
     } else if constexpr (MODE == EPI_UNPATCH) {
@@ -147,7 +150,7 @@ struct AttnParams {
   int q_tokens, q_gstride, q_istride;
   int k_tokens, k_gstride, k_istride;
   int kv_split, kv_shared_tail;
-  float scale_log2;   // softmax scale times log2(e)
+  float scale_log2;   // factor still to be applied to q.k: scale*log2(e), or 1 if q already carries it
 };
 
 // ---------------------------------------------------------------- launchers (defined in the .hip files)

@@ -295,6 +295,7 @@ EpiParams heads_epi(const Ctx& c, void* q, void* k, void* v, int which0, int tok
   ep.which0 = which0;
   ep.D = c.m->cfg.hidden; ep.heads = c.m->cfg.heads; ep.hd = c.m->hd;
   ep.tokens = tokens;
+  ep.qscale = (float)(1.4426950408889634 / std::sqrt((double)c.m->hd));
   return ep;
 }
 
@@ -351,7 +352,7 @@ int self_attention_branch(const Ctx& c, const Linear& qkv, const Linear& proj, c
   else if (mode == 1) { ap.groups = m->S; ap.nq = ap.nk = cf.frames; ap.q_gstride = ap.k_gstride = 1; ap.q_istride = ap.k_istride = m->S; }
   else { ap.groups = 1; ap.nq = ap.nk = m->Ns; ap.q_gstride = ap.k_gstride = 0; ap.q_istride = ap.k_istride = 1; }
   ap.kv_split = 0; ap.kv_shared_tail = 0;
-  ap.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)m->hd));
+  ap.scale_log2 = 1.0f;                  // q was stored pre-scaled by the QKV epilogue
   {
     ProfScope ps(c, mode == 0 ? PC_ATTN_SPATIAL : mode == 1 ? PC_ATTN_TEMPORAL : PC_ATTN_FULL);
     HIP_TRY(launch_attention(m->bf16, ap, 0, c.s));
@@ -380,7 +381,7 @@ int cross_attention_branch(const Ctx& c, const Block& b, int layer) {
   ap.q_tokens = m->Ns; ap.q_gstride = 0; ap.q_istride = 1;
   ap.k_tokens = cf.text_len; ap.k_gstride = 0; ap.k_istride = 1;
   ap.kv_split = c.R; ap.kv_shared_tail = c.use_cfg;      // guidance rows all read the null text
-  ap.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)m->hd));
+  ap.scale_log2 = 1.0f;
   {
     ProfScope ps(c, PC_ATTN_CROSS);
     HIP_TRY(launch_attention(m->bf16, ap, 0, c.s));
