@@ -117,6 +117,15 @@ def test_attention_plain(fc, G, nq, nk, d, bf):
     assert rel_l2(got, want) < (5e-3 if bf else 2e-5)
 
 
+@pytest.mark.parametrize("G,nq,nk", [(2, 600, 333), (1, 1, 1), (3, 64, 64), (1, 1100, 1000), (2, 513, 129)])
+@pytest.mark.parametrize("gain", [1.0, 2.5])
+def test_attention_pingpong_bf16(fc, G, nq, nk, gain):
+    got, want = _attn_case(fc, G, nq, nk, 64, gain, True, 2)
+    assert np.all(np.isfinite(got))
+    assert rel_l2(got, want) < 1e-2, (rel_l2(got, want), max_abs(got, want))
+    assert max_abs(got, want) < 5e-2
+
+
 def test_attention_rows_are_convex_combinations(fc):
     """Property that holds at any size: with all-ones V every output is exactly 1
     (softmax rows sum to 1), also across a ragged last key tile."""
