@@ -24,6 +24,26 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
 
+def measured_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None
+    when there is none or the kernel source has changed since the counters were taken."""
+    import glob
+    import hashlib
+    for path in glob.glob(os.path.join(ROOT, "profiles", "*hbm_traffic.txt")):
+        kv = {}
+        for line in open(path):
+            if "=" in line and not line.startswith("#"):
+                k, v = line.split("=", 1)
+                kv[k.strip()] = v.strip()
+        if f"{kernel}.fetch_bytes" not in kv:
+            continue
+        src = os.path.join(ROOT, "paper_2501_04012_amd", "csrc", "attention.hip")
+        if hashlib.sha256(open(src, "rb").read()).hexdigest() != kv.get(f"{kernel}.source_sha256"):
+            return None
+        return float(kv[f"{kernel}.fetch_bytes"]) + float(kv[f"{kernel}.write_bytes"])
+    return None
+
+
 def cpu_baseline(w, weights, lat, cond):
     """The oracle (fp32 arithmetic) on the host cores, on a bounded sample of the same
     workload, converted to steps/s."""
@@ -74,6 +94,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run one plain device copy of this size (a known-size kernel for scaling HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
@@ -99,6 +121,13 @@ def main():
     d_cond = torch.from_numpy(cond).cuda()
     d_null = torch.from_numpy(null).cuda() if use_cfg else None
     d_lat = d_lat0.clone()
+
+    if args.copy_calibration_mib:
+        src = torch.empty(args.copy_calibration_mib << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         d_lat.copy_(d_lat0)
@@ -144,7 +173,7 @@ def main():
     if dom in per_launch_flops:
         ach = per_launch_flops[dom] / (kernels[dom]["avg_launch_ms"] * 1e-3) / 1e12
         roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / PEAK_BF16_TFLOPS, "traffic": None}
+                    "frac": ach / PEAK_BF16_TFLOPS, "traffic": measured_traffic(dom)}
     else:
         roofline = {"kernel": dom, "bound": "hbm", "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": None, "traffic": None}

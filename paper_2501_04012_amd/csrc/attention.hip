@@ -31,14 +31,38 @@ __device__ __forceinline__ long long xcd_work_item(long long total) {
 }
 
 // ---------------------------------------------------------------- plain kernel
+// One thread per query row, online softmax in fp32, rows read with 16-byte loads.
+// Thread order follows memory order: for strided sequences (temporal attention: token
+// stride S) neighbouring threads take neighbouring groups, so their q/k/v rows are
+// adjacent in memory; for contiguous sequences neighbouring threads take neighbouring
+// queries of one group and share its key rows.
+template <typename T, int HD>
+__device__ __forceinline__ void load_row(const T* __restrict__ src, float (&dst)[HD]) {
+  constexpr int V = 16 / sizeof(T);
+  static_assert(HD % V == 0, "row must be a whole number of 16-byte chunks");
+#pragma unroll
+  for (int c = 0; c < HD; c += V) {
+    if constexpr (sizeof(T) == 2) {
+      bf16x8 v = *(const bf16x8*)(src + c);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dst[c + e] = (float)v[e];
+    } else {
+      f32x4 v = *(const f32x4*)(src + c);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) dst[c + e] = v[e];
+    }
+  }
+}
+
 template <typename T, int HD>
 __global__ __launch_bounds__(64) void k_attn_plain(AttnParams p) {
   const long long gid = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   const long long total = (long long)p.B * p.heads * p.groups * p.nq;
   if (gid >= total) return;
-  const int i = (int)(gid % p.nq);
-  long long r = gid / p.nq;
-  const int g = (int)(r % p.groups); r /= p.groups;
+  int i, g;
+  long long r;
+  if (p.q_istride == 1) { i = (int)(gid % p.nq); r = gid / p.nq; g = (int)(r % p.groups); r /= p.groups; }
+  else { g = (int)(gid % p.groups); r = gid / p.groups; i = (int)(r % p.nq); r /= p.nq; }
   const int head = (int)(r % p.heads);
   const int b = (int)(r / p.heads);
   const int kb = key_batch(p, b);
@@ -48,23 +72,25 @@ __global__ __launch_bounds__(64) void k_attn_plain(AttnParams p) {
   const T* kbase = (const T*)p.k + ((size_t)kb * p.heads + head) * (size_t)p.k_tokens * HD;
   const T* vbase = (const T*)p.v + ((size_t)kb * p.heads + head) * (size_t)p.k_tokens * HD;
 
-  float qv[HD], o[HD];
+  float qv[HD], o[HD], row[HD];
+  load_row<T, HD>(q, qv);
 #pragma unroll
-  for (int c = 0; c < HD; ++c) { qv[c] = to_f32(q[c]); o[c] = 0.0f; }
+  for (int c = 0; c < HD; ++c) o[c] = 0.0f;
   float m = -INFINITY, l = 0.0f;
   for (int j = 0; j < p.nk; ++j) {
     const int ktok = g * p.k_gstride + j * p.k_istride;
-    const T* kr = kbase + (size_t)ktok * HD;
+    load_row<T, HD>(kbase + (size_t)ktok * HD, row);
     float s = 0.0f;
 #pragma unroll
-    for (int c = 0; c < HD; ++c) s += qv[c] * to_f32(kr[c]);
+    for (int c = 0; c < HD; ++c) s += qv[c] * row[c];
     s *= p.scale_log2;
     const float mn = fmaxf(m, s);
     const float alpha = exp2f(m - mn);     // m = -inf on the first key: exp2(-inf) = 0
     const float pj = exp2f(s - mn);
     l = l * alpha + pj;
+    load_row<T, HD>(vbase + (size_t)ktok * HD, row);
 #pragma unroll
-    for (int c = 0; c < HD; ++c) o[c] = o[c] * alpha + pj * to_f32(vbase[(size_t)ktok * HD + c]);
+    for (int c = 0; c < HD; ++c) o[c] = o[c] * alpha + pj * row[c];
     m = mn;
   }
   const float inv = 1.0f / l;
@@ -81,16 +107,121 @@ static hipError_t run_plain(const AttnParams& p, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- short strided sequences (temporal)
+// Temporal attention: S independent sequences of T <= 32 tokens per (batch, head), token
+// t of sequence s being row t*S + s.  A workgroup takes SB = 8 neighbouring sequences:
+// for each t their rows are one contiguous run of SB*HD elements, fetched with 16-byte
+// loads into LDS (q, k, v tiles [T][SB][HD]); thread (t, s) then runs the plain online
+// softmax for its query against the T keys of its sequence out of LDS.  The work is a
+// few flops per byte: the kernel is bound by reading q, k, v and writing o once.
+constexpr int TS_SB = 8;
+template <typename T, int HD>
+__global__ __launch_bounds__(256) void k_attn_short_strided(AttnParams p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_ts[];
+  T* qs = (T*)smem_ts;
+  const int Tn = p.nq;                       // == nk
+  const int tile = Tn * TS_SB * HD;          // elements per tensor tile
+  T* ks = qs + tile;
+  T* vs = ks + tile;
+  const int sblocks = (p.groups + TS_SB - 1) / TS_SB;
+  int bid = blockIdx.x;
+  const int sb = bid % sblocks; bid /= sblocks;
+  const int head = bid % p.heads;
+  const int b = bid / p.heads;
+  const int s0 = sb * TS_SB;
+  const size_t bh = ((size_t)b * p.heads + head) * (size_t)p.q_tokens;
+  const T* qg = (const T*)p.q + bh * HD;
+  const T* kg = (const T*)p.k + bh * HD;
+  const T* vg = (const T*)p.v + bh * HD;
+
+  constexpr int V = 16 / sizeof(T);
+  constexpr int CPR = HD / V;                // 16-byte chunks per row
+  const int chunks = Tn * TS_SB * CPR;
+  for (int ch = threadIdx.x; ch < chunks; ch += blockDim.x) {
+    const int c = ch % CPR, r = ch / CPR;
+    const int s = r % TS_SB, t = r / TS_SB;
+    int sg = s0 + s; sg = sg < p.groups ? sg : p.groups - 1;     // clamp: rows past the last sequence are never stored
+    const size_t goff = ((size_t)t * p.q_istride + sg) * HD + c * V;
+    const int loff = (t * TS_SB + s) * HD + c * V;
+    *(f32x4*)(qs + loff) = *(const f32x4*)(qg + goff);
+    *(f32x4*)(ks + loff) = *(const f32x4*)(kg + goff);
+    *(f32x4*)(vs + loff) = *(const f32x4*)(vg + goff);
+  }
+  __syncthreads();
+
+  const int s = threadIdx.x % TS_SB, tq = threadIdx.x / TS_SB;
+  if (tq >= Tn || s0 + s >= p.groups) return;
+  float qv[HD], o[HD], row[HD];
+  load_row<T, HD>(qs + (tq * TS_SB + s) * HD, qv);
+#pragma unroll
+  for (int c = 0; c < HD; ++c) o[c] = 0.0f;
+  float m = -INFINITY, l = 0.0f;
+  for (int j = 0; j < Tn; ++j) {
+    load_row<T, HD>(ks + (j * TS_SB + s) * HD, row);
+    float sc = 0.0f;
+#pragma unroll
+    for (int c = 0; c < HD; ++c) sc += qv[c] * row[c];
+    sc *= p.scale_log2;
+    const float mn = fmaxf(m, sc);
+    const float alpha = exp2f(m - mn);
+    const float pj = exp2f(sc - mn);
+    l = l * alpha + pj;
+    load_row<T, HD>(vs + (j * TS_SB + s) * HD, row);
+#pragma unroll
+    for (int c = 0; c < HD; ++c) o[c] = o[c] * alpha + pj * row[c];
+    m = mn;
+  }
+  const float inv = 1.0f / l;
+  const int tok = tq * p.q_istride + s0 + s;
+  T* out = (T*)p.out + ((size_t)b * p.q_tokens + tok) * ((size_t)p.heads * HD) + (size_t)head * HD;
+#pragma unroll
+  for (int c = 0; c < HD; c += V) {
+    if constexpr (sizeof(T) == 2) {
+      bf16x8 ov;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ov[e] = (bf16_t)(o[c + e] * inv);
+      *(bf16x8*)(out + c) = ov;
+    } else {
+      f32x4 ov;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ov[e] = o[c + e] * inv;
+      *(f32x4*)(out + c) = ov;
+    }
+  }
+}
+
+static bool short_strided_ok(const AttnParams& p, size_t esz) {
+  return p.nq == p.nk && p.nq >= 1 && p.nq * TS_SB <= 256 && p.q_gstride == 1 && p.k_gstride == 1 &&
+         p.q_istride == p.k_istride && p.q_istride == p.groups && p.q_tokens == p.k_tokens && !p.kv_shared_tail &&
+         (size_t)3 * p.nq * TS_SB * p.hd * esz <= 64 * 1024;
+}
+
+template <typename T, int HD>
+static hipError_t run_short_strided(const AttnParams& p, hipStream_t s) {
+  const long long blocks = (long long)p.B * p.heads * ((p.groups + TS_SB - 1) / TS_SB);
+  if (blocks == 0) return hipSuccess;
+  const size_t smem = (size_t)3 * p.nq * TS_SB * HD * sizeof(T);
+  const int threads = (p.nq * TS_SB + 63) / 64 * 64;
+  k_attn_short_strided<T, HD><<<(unsigned)blocks, threads, smem, s>>>(p);
+  return hipGetLastError();
+}
+
+template <typename T, int HD>
+static hipError_t run_non_mfma(const AttnParams& p, bool allow_short, hipStream_t s) {
+  if (allow_short && short_strided_ok(p, sizeof(T))) return run_short_strided<T, HD>(p, s);
+  return run_plain<T, HD>(p, s);
+}
+
 template <typename T>
-static hipError_t dispatch_plain(const AttnParams& p, hipStream_t s) {
+static hipError_t dispatch_plain(const AttnParams& p, bool allow_short, hipStream_t s) {
   switch (p.hd) {
-    case 8: return run_plain<T, 8>(p, s);
-    case 16: return run_plain<T, 16>(p, s);
-    case 32: return run_plain<T, 32>(p, s);
-    case 64: return run_plain<T, 64>(p, s);
-    case 72: return run_plain<T, 72>(p, s);
-    case 96: return run_plain<T, 96>(p, s);
-    case 128: return run_plain<T, 128>(p, s);
+    case 8: return run_non_mfma<T, 8>(p, allow_short, s);
+    case 16: return run_non_mfma<T, 16>(p, allow_short, s);
+    case 32: return run_non_mfma<T, 32>(p, allow_short, s);
+    case 64: return run_non_mfma<T, 64>(p, allow_short, s);
+    case 72: return run_non_mfma<T, 72>(p, allow_short, s);
+    case 96: return run_non_mfma<T, 96>(p, allow_short, s);
+    case 128: return run_non_mfma<T, 128>(p, allow_short, s);
   }
   return hipErrorInvalidValue;
 }
@@ -766,14 +897,16 @@ static bool flash_ok(const AttnParams& p) {
 }
 
 hipError_t launch_attention(int bf16, const AttnParams& p, int impl, hipStream_t s) {
-  if (!bf16) return dispatch_plain<float>(p, s);
+  // every kernel reads rows with 16-byte loads
+  if ((((uintptr_t)p.q | (uintptr_t)p.k | (uintptr_t)p.v | (uintptr_t)p.out) & 15) != 0) return hipErrorInvalidValue;
+  if (!bf16) return dispatch_plain<float>(p, impl != 1, s);
   if ((impl == 0 || impl == 2 || impl == 3) && flash_ok(p)) {
     if (impl == 3 && p.hd == 64) return run_flash<64>(p, s);
     if (impl == 2 && p.hd == 64) return run_pingpong(p, s);
     if (p.hd == 64) return run_flash<64>(p, s);
     if (p.hd == 72) return run_flash<72>(p, s);
   }
-  return dispatch_plain<bf16_t>(p, s);
+  return dispatch_plain<bf16_t>(p, impl != 1, s);
 }
 
 }  // namespace fc

@@ -740,7 +740,7 @@ int fc_op_attention(int32_t dtype, const void* q, const void* k, const void* v, 
   ap.k_tokens = nk; ap.k_gstride = 0; ap.k_istride = 1;
   ap.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)d));
   hipError_t e = launch_attention(dtype == FC_BF16, ap, impl, (hipStream_t)stream);
-  if (e == hipErrorInvalidValue) return fail(FC_ERR_UNSUPPORTED, "head dim not supported");
+  if (e == hipErrorInvalidValue) return fail(FC_ERR_UNSUPPORTED, "head dim not supported or pointers not 16-byte aligned");
   HIP_TRY(e);
   return FC_OK;
 }

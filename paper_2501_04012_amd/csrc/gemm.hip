@@ -1,5 +1,6 @@
 // Linear layers: C[M,N] = A[M,K] * Wt[N,K]^T with fused epilogues.
-//   bf16: MFMA (v_mfma_f32_32x32x16_bf16) kernel, LDS-tiled, fp32 accumulation.
+//   bf16: MFMA (v_mfma_f32_32x32x16_bf16) kernel, operands DMA'd into swizzled LDS tiles,
+//         fp32 accumulation.
 //   fp32: plain LDS-tiled FMA kernel (the fp32 configuration is tiny and
 //         launch-bound; it exists for the 1e-4 parity bar, not for speed).
 // Both operands are contiguous along K ("TN" form): activations are [tokens, K]
@@ -9,8 +10,12 @@
 namespace fc {
 
 // ---------------------------------------------------------------- bf16 MFMA kernel, direct-to-LDS
-// Same tiling and MFMA layout as k_gemm_bf16 below, but the operand tiles go from
-// global memory straight into LDS (global_load_lds_dwordx4: lane l's 16 bytes land at
+// Block tile BM x BN x BK, NW = WR x WC waves, each wave owns a (BM/WR) x (BN/WC) tile built
+// from 32x32 MFMA accumulators.  MFMA operand layout (32x32x16, wave64), lane = i + 32*h:
+//   A: row i of the 32-row tile, k = 8h .. 8h+7        (8 bf16 = one 16-byte LDS read)
+//   B: column i of the 32-col tile, k = 8h .. 8h+7
+//   D: column i, rows 8g + 4h + e for register 4g + e   (g, e in 0..3)
+// The operand tiles go from global memory straight into LDS (global_load_lds_dwordx4: lane l's 16 bytes land at
 // base + 16 l), S stages deep, with no register staging and no ds_write.
 //
 // LDS layout of a stage: BM rows of A then BN rows of B, BK*2 bytes each, unpadded.
@@ -23,6 +28,12 @@ namespace fc {
 // Pipeline per K tile: wait until this tile's loads have landed (vmcnt), barrier
 // (publishes every wave's part and frees the stage read in the previous iteration),
 // issue the loads of tile kt+S-1 into that stage, then run the MFMAs of tile kt.
+//
+// Tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2.
+// Id -> tile index is chosen so that 32 workgroups running together on one XCD hold 32
+// consecutive tile indices, and consecutive indices walk GM = 8 tile rows before moving to
+// the next tile column: an XCD works on an 8 x 4 patch of C and streams 8 + 4 operand
+// panels through its L2 instead of 1 + 32.
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void gbl_void;
 
@@ -148,146 +159,6 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
     }
 }
 
-// ---------------------------------------------------------------- bf16 MFMA kernel, register-staged
-// Block tile BM x BN x BK, NW = WR x WC waves, each wave owns a (BM/WR) x (BN/WC)
-// tile built from 32x32 MFMA accumulators.
-//
-// MFMA operand layout (32x32x16, wave64), lane = i + 32*h:
-//   A: row i of the 32-row tile, k = 8h .. 8h+7        (8 bf16 = one 16-byte LDS read)
-//   B: column i of the 32-col tile, k = 8h .. 8h+7
-//   D: column i, rows 8g + 4h + e for register 4g + e   (g, e in 0..3)
-// Global -> register -> LDS staging, double-buffered LDS: the loads of tile kt+1
-// are issued before the MFMAs of tile kt and written to the other buffer after,
-// one barrier per K tile.
-//
-// Tile order.  Workgroup ids are dealt round-robin to the 8 XCDs, each with its
-// own L2, and an XCD runs 32 workgroups at a time.  Id -> tile index is chosen so
-// that the 32 concurrent workgroups of one XCD hold 32 consecutive tile indices,
-// and consecutive indices walk GM = 8 tile rows before moving to the next tile
-// column: an XCD works on an 8 x 4 patch of C and streams 8 + 4 operand panels
-// through its L2 instead of 1 + 32.
-template <int BM, int BN, int BK, int WR, int WC, typename Epi>
-__global__ __launch_bounds__(WR * WC * 64) void k_gemm_bf16(const bf16_t* __restrict__ A,
-                                                            const bf16_t* __restrict__ Wt, int M, int N, int K,
-                                                            int tiles_m, int tiles_n, Epi epi) {
-  constexpr int NT = WR * WC * 64;            // threads
-  constexpr int LDT = BK + 8;                 // padded LDS row (elements)
-  constexpr int WTM = BM / WR, WTN = BN / WC; // wave tile
-  constexpr int TM = WTM / 32, TN = WTN / 32;
-  constexpr int CPR = BK / 8;                 // 16-byte chunks per tile row
-  constexpr int A_CHUNKS = BM * CPR / NT, B_CHUNKS = BN * CPR / NT;
-  static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/threads mismatch");
-
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  bf16_t* As = (bf16_t*)smem_raw;                        // [2][BM][LDT]
-  bf16_t* Bs = As + 2 * BM * LDT;                        // [2][BN][LDT]
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wr = wave / WC, wc = wave % WC;
-  const int li = lane & 31, lh = lane >> 5;
-
-  // workgroup id -> tile
-  const int total = tiles_m * tiles_n;
-  const int bid = blockIdx.x;
-  const int xcd = bid & 7, local = bid >> 3;
-  const int t = ((local >> 5) * 8 + xcd) * 32 + (local & 31);
-  if (t >= total) return;
-  constexpr int GM = 8;
-  const int per_group = GM * tiles_n;
-  const int group = t / per_group;
-  const int first_m = group * GM;
-  const int gsz = min(tiles_m - first_m, GM);
-  const int tm = first_m + (t % per_group) % gsz;
-  const int tn = (t % per_group) / gsz;
-  const int bm0 = tm * BM, bn0 = tn * BN;
-
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-  bf16x8 ra[A_CHUNKS], rb[B_CHUNKS];
-  const int nkt = K / BK;
-
-  // per-thread source rows (clamped: rows past M / N are loaded but never stored)
-  const bf16_t* ga[A_CHUNKS];
-  const bf16_t* gb[B_CHUNKS];
-#pragma unroll
-  for (int c = 0; c < A_CHUNKS; ++c) {
-    int ch = tid + c * NT, row = ch / CPR, kc = ch % CPR;
-    int gm = bm0 + row; gm = gm < M ? gm : M - 1;
-    ga[c] = A + (size_t)gm * K + kc * 8;
-  }
-#pragma unroll
-  for (int c = 0; c < B_CHUNKS; ++c) {
-    int ch = tid + c * NT, row = ch / CPR, kc = ch % CPR;
-    int gn = bn0 + row; gn = gn < N ? gn : N - 1;
-    gb[c] = Wt + (size_t)gn * K + kc * 8;
-  }
-  auto gload = [&](int kt) {
-#pragma unroll
-    for (int c = 0; c < A_CHUNKS; ++c) ra[c] = *(const bf16x8*)(ga[c] + (size_t)kt * BK);
-#pragma unroll
-    for (int c = 0; c < B_CHUNKS; ++c) rb[c] = *(const bf16x8*)(gb[c] + (size_t)kt * BK);
-  };
-  auto sstore = [&](int buf) {
-    bf16_t* a = As + buf * BM * LDT;
-    bf16_t* b = Bs + buf * BN * LDT;
-#pragma unroll
-    for (int c = 0; c < A_CHUNKS; ++c) {
-      int ch = tid + c * NT, row = ch / CPR, kc = ch % CPR;
-      *(bf16x8*)(a + row * LDT + kc * 8) = ra[c];
-    }
-#pragma unroll
-    for (int c = 0; c < B_CHUNKS; ++c) {
-      int ch = tid + c * NT, row = ch / CPR, kc = ch % CPR;
-      *(bf16x8*)(b + row * LDT + kc * 8) = rb[c];
-    }
-  };
-
-  gload(0);
-  sstore(0);
-  __syncthreads();
-
-  for (int kt = 0; kt < nkt; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nkt) gload(kt + 1);
-    const bf16_t* a = As + buf * BM * LDT + (wr * WTM + li) * LDT + lh * 8;
-    const bf16_t* b = Bs + buf * BN * LDT + (wc * WTN + li) * LDT + lh * 8;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[TM], fb[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8*)(a + i * 32 * LDT + ks * 16);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = *(const bf16x8*)(b + j * 32 * LDT + ks * 16);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nkt) sstore(buf ^ 1);
-    __syncthreads();
-  }
-
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = bn0 + wc * WTN + j * 32 + li;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int m0 = bm0 + wr * WTM + i * 32 + g * 8 + lh * 4;
-        float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-        epi.store4(m0, n, v);
-      }
-    }
-}
-
 // ---------------------------------------------------------------- plain kernel (any T, any shape)
 // 64x64 block tile, BK = 16, 256 threads each owning a 4(row) x 4(col) micro-tile.
 template <typename T, typename Epi>
@@ -329,25 +200,6 @@ __global__ __launch_bounds__(256) void k_gemm_plain(const T* __restrict__ A, con
 }
 
 // ---------------------------------------------------------------- dispatch
-template <int BM, int BN, int BK, int WR, int WC, int MODE>
-static hipError_t run_mfma(const void* A, const void* Wt, int M, int N, int K, const EpiParams& ep, hipStream_t s) {
-  using Epi = Epilogue<bf16_t, MODE>;
-  Epi epi{ep, M, N};
-  constexpr size_t smem = (size_t)2 * (BM + BN) * (BK + 8) * sizeof(bf16_t);
-  auto kern = k_gemm_bf16<BM, BN, BK, WR, WC, Epi>;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  const int tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
-  const long long total = (long long)tiles_m * tiles_n;
-  const unsigned grid = (unsigned)((total + 255) / 256 * 256);   // whole rounds of 8 XCDs x 32 workgroups
-  kern<<<grid, WR * WC * 64, smem, s>>>((const bf16_t*)A, (const bf16_t*)Wt, M, N, K, tiles_m, tiles_n, epi);
-  return hipGetLastError();
-}
-
 template <int BM, int BN, int BK, int WR, int WC, int S, int MODE>
 static hipError_t run_dlds(const void* A, const void* Wt, int M, int N, int K, const EpiParams& ep, hipStream_t s) {
   using Epi = Epilogue<bf16_t, MODE>;
@@ -382,10 +234,14 @@ static hipError_t dispatch_mode(int bf16, const void* A, const void* Wt, int M, 
   if (!bf16) return run_plain<float, MODE>(A, Wt, M, N, K, ep, s);
   const bool aligned = (((uintptr_t)A | (uintptr_t)Wt) & 15) == 0;
   if (K % 64 != 0 || !aligned || N < 32) return run_plain<bf16_t, MODE>(A, Wt, M, N, K, ep, s);
-  // tile choice: the big tile when it still gives every CU work, else the small one
-  const long long big_tiles = (long long)ceil_div(M, 256) * ceil_div(N, 256);
-  if (big_tiles >= 512) return run_dlds<256, 256, 64, 4, 2, 2, MODE>(A, Wt, M, N, K, ep, s);
-  return run_mfma<128, 128, 64, 2, 2, MODE>(A, Wt, M, N, K, ep, s);
+  // Tile choice.  256x256 (8 waves, one workgroup per CU) has the best operand reuse but
+  // needs several rounds of tiles per CU and wastes the ragged part of N; 128x128 (4
+  // waves, two workgroups per CU, so one's epilogue overlaps the other's main loop) wins
+  // for narrow or short-K products.  Thresholds from timings of the workload shapes.
+  const long long tiles256 = (long long)ceil_div(M, 256) * ceil_div(N, 256);
+  const double waste = (double)ceil_div(N, 256) * 256.0 / N - 1.0;
+  if (tiles256 >= 600 && (waste <= 0.05 || K >= 2048)) return run_dlds<256, 256, 64, 4, 2, 2, MODE>(A, Wt, M, N, K, ep, s);
+  return run_dlds<128, 128, 64, 2, 2, 2, MODE>(A, Wt, M, N, K, ep, s);
 }
 
 hipError_t launch_gemm(int bf16, int mode, const void* A, const void* Wt, int M, int N, int K, const EpiParams& ep,
