@@ -60,7 +60,7 @@ enum { FC_F32 = 0,   /* fp32 weights, activations and arithmetic */
 /* Model shape.  Latent is [frames, height, width, channels]; patches are
  * patch x patch in space (temporal patch 1), so a frame has
  * S = (height/patch)*(width/patch) tokens and the video N = frames*S tokens in
- * (t, h', w') row-major order.  hidden % heads == 0, hidden % 4 == 0,
+ * (t, h', w') row-major order.  hidden % heads == 0, hidden % 4 == 0, hidden <= 4096,
  * height % patch == 0, width % patch == 0, t_embed_dim even. */
 typedef struct {
   int32_t frames, height, width, channels, patch;
@@ -167,15 +167,11 @@ int fc_profile_read(fc_model* m, int32_t n, double* ms_out, int64_t* launches_ou
  * elements for every tensor marked "act". ------------------------------------- */
 
 /* out[M,N] (act) = epilogue(A[M,K] (act) * Wt[N,K]^T (act) + bias[N] (f32)).
- * epilogue 0: bias only; 1: bias + GELU(tanh).  The network's linear layers. */
-int fc_op_linear(int32_t dtype, const void* A, const void* Wt, const float* bias, void* out,
-                 int32_t M, int32_t N, int32_t K, int32_t epilogue, void* hip_stream);
-
-/* x[M,N] (f32) += gate[N] (f32, NULL = ones) * (A[M,K] * Wt[N,K]^T + bias[N]):
- * the gated residual epilogue of the out-projection and fc2 layers. */
-int fc_op_linear_residual(int32_t dtype, const void* A, const void* Wt, const float* bias,
-                          const float* gate, float* x, int32_t M, int32_t N, int32_t K,
-                          void* hip_stream);
+ * epilogue 0: bias only; 1: bias + GELU(tanh); 2: gate[N] (f32, NULL = ones) times
+ * (bias added): the gated branch output whose residual add the next LayerNorm performs.
+ * The network's linear layers. */
+int fc_op_linear(int32_t dtype, const void* A, const void* Wt, const float* bias, const float* gate,
+                 void* out, int32_t M, int32_t N, int32_t K, int32_t epilogue, void* hip_stream);
 
 /* Unmasked softmax(q k^T / sqrt(d)) v for G independent problems (one per
  * sequence and head).  q [G, nq, d], k [G, nk, d], v [G, nk, d], out [G, nq, d]
@@ -184,10 +180,12 @@ int fc_op_linear_residual(int32_t dtype, const void* A, const void* Wt, const fl
 int fc_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* out,
                     int32_t G, int32_t nq, int32_t nk, int32_t d, int32_t impl, void* hip_stream);
 
-/* out[M,D] (act) = LayerNorm(x[M,D] (f32)) * (1 + scale[D]) + shift[D]
- * (shift/scale f32, both NULL = plain LayerNorm); eps as in the model config. */
-int fc_op_layernorm_modulate(int32_t dtype, const float* x, const float* shift, const float* scale,
-                             void* out, int32_t M, int32_t D, float eps, void* hip_stream);
+/* If y (act, [M,D]) is not NULL: x[M,D] (f32) <- x + y first (the pending branch output).
+ * Then out[M,D] (act) = LayerNorm(x) * (1 + scale[D]) + shift[D] (shift/scale f32, both
+ * NULL = plain LayerNorm); D a multiple of 4, at most 4096. */
+int fc_op_layernorm_modulate(int32_t dtype, float* x, const void* y, const float* shift,
+                             const float* scale, void* out, int32_t M, int32_t D, float eps,
+                             void* hip_stream);
 
 /* Fused guidance + DDIM update on n elements per request, R requests:
  * eps = eps_u + s (eps_c - eps_u) (eps_u NULL: eps = eps_c);

@@ -55,14 +55,12 @@ EXPORTS = {
     "fc_profile_enable": [C.c_void_p, C.c_int32],
     "fc_profile_categories": [],
     "fc_profile_read": [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)],
-    "fc_op_linear": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
-                     C.c_int32, C.c_void_p],
-    "fc_op_linear_residual": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
-                              C.c_int32, C.c_int32, C.c_void_p],
+    "fc_op_linear": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                     C.c_int32, C.c_int32, C.c_void_p],
     "fc_op_attention": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                         C.c_int32, C.c_int32, C.c_void_p],
-    "fc_op_layernorm_modulate": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
-                                 C.c_float, C.c_void_p],
+    "fc_op_layernorm_modulate": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                 C.c_int32, C.c_float, C.c_void_p],
     "fc_op_cfg_ddim": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_float,
                        C.POINTER(C.c_float), C.c_void_p],
 }
@@ -193,14 +191,9 @@ def fc_profile_read(model: int):
     return {fc_profile_category_name(i): (ms[i], cnt[i]) for i in range(n)}
 
 
-def fc_op_linear(dtype, A, Wt, bias, out, M, N, K, epilogue, stream=None) -> None:
-    _check(_lib.fc_op_linear(dtype, _ptr(A), _ptr(Wt), _ptr(bias), _ptr(out), M, N, K, epilogue, _stream(stream)),
-           "fc_op_linear")
-
-
-def fc_op_linear_residual(dtype, A, Wt, bias, gate, x, M, N, K, stream=None) -> None:
-    _check(_lib.fc_op_linear_residual(dtype, _ptr(A), _ptr(Wt), _ptr(bias), _ptr(gate), _ptr(x), M, N, K,
-                                      _stream(stream)), "fc_op_linear_residual")
+def fc_op_linear(dtype, A, Wt, bias, gate, out, M, N, K, epilogue, stream=None) -> None:
+    _check(_lib.fc_op_linear(dtype, _ptr(A), _ptr(Wt), _ptr(bias), _ptr(gate), _ptr(out), M, N, K, epilogue,
+                             _stream(stream)), "fc_op_linear")
 
 
 def fc_op_attention(dtype, q, k, v, out, G, nq, nk, d, impl=0, stream=None) -> None:
@@ -208,8 +201,8 @@ def fc_op_attention(dtype, q, k, v, out, G, nq, nk, d, impl=0, stream=None) -> N
            "fc_op_attention")
 
 
-def fc_op_layernorm_modulate(dtype, x, shift, scale, out, M, D, eps, stream=None) -> None:
-    _check(_lib.fc_op_layernorm_modulate(dtype, _ptr(x), _ptr(shift), _ptr(scale), _ptr(out), M, D, eps,
+def fc_op_layernorm_modulate(dtype, x, y, shift, scale, out, M, D, eps, stream=None) -> None:
+    _check(_lib.fc_op_layernorm_modulate(dtype, _ptr(x), _ptr(y), _ptr(shift), _ptr(scale), _ptr(out), M, D, eps,
                                          _stream(stream)), "fc_op_layernorm_modulate")
 
 

@@ -53,17 +53,16 @@ inline size_t round_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
 enum EpiMode : int {
   EPI_STORE = 0,     // out[m,n] = acc + bias
   EPI_GELU = 1,      // out[m,n] = gelu(acc + bias)
-  EPI_RESID = 2,     // x[m,n] += gate[n] * (acc + bias)     (gate NULL: 1)
+  EPI_GATE = 2,      // out[m,n] = gate[n] * (acc + bias)    (gate NULL: 1); the residual add is the next LN's
   EPI_HEADS = 3,     // scatter into per-head q / k / v tensors
   EPI_UNPATCH = 4    // scatter token rows back into a latent-shaped fp32 tensor
 };
 
 struct EpiParams {
   const float* bias = nullptr;   // [N]
-  void* out = nullptr;           // EPI_STORE / EPI_GELU: act [M, ldo]
+  void* out = nullptr;           // EPI_STORE / EPI_GELU / EPI_GATE: act [M, ldo]
   int ldo = 0;
-  float* x = nullptr;            // EPI_RESID: fp32 [M, ldo]
-  const float* gate = nullptr;   // EPI_RESID: [N] or NULL
+  const float* gate = nullptr;   // EPI_GATE: [N] or NULL
   // EPI_HEADS: column n -> which = which0 + n / D (0 q, 1 k, 2 v), head = (n % D) / hd.
   // Row m -> (b, tok) = (m / tokens, m % tokens).
   // q, k, v: [b, head, tok, hd].
@@ -84,23 +83,17 @@ struct Epilogue {
   __device__ __forceinline__ void store4(int m0, int n, const float (&acc)[4]) const {
     if (n >= Nvalid || m0 >= Mvalid) return;
     const float b = P.bias ? P.bias[n] : 0.0f;
-    if constexpr (MODE == EPI_STORE || MODE == EPI_GELU) {
+    if constexpr (MODE == EPI_STORE || MODE == EPI_GELU || MODE == EPI_GATE) {
       T* o = (T*)P.out;
+      float g = 1.0f;
+      if constexpr (MODE == EPI_GATE) g = P.gate ? P.gate[n] : 1.0f;
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         if (m0 + e < Mvalid) {
           float v = acc[e] + b;
           if constexpr (MODE == EPI_GELU) v = gelu_tanh_f(v);
+          if constexpr (MODE == EPI_GATE) v *= g;
           o[(size_t)(m0 + e) * P.ldo + n] = from_f32<T>(v);
-        }
-      }
-    } else if constexpr (MODE == EPI_RESID) {
-      const float g = P.gate ? P.gate[n] : 1.0f;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        if (m0 + e < Mvalid) {
-          size_t idx = (size_t)(m0 + e) * P.ldo + n;
-          P.x[idx] = P.x[idx] + g * (acc[e] + b);
         }
       }
     } else if constexpr (MODE == EPI_HEADS) {
@@ -166,7 +159,7 @@ hipError_t launch_gemv(int bf16, const float* in, int K, const void* Wt, const f
 hipError_t launch_patch_embed(const float* latent, int R, int B, const float* Wp, const float* bp,
                               const float* pos_sp, const float* pos_t, float* x, int T, int H, int W, int C,
                               int p, int D, int rows_per_b, int row_off, hipStream_t s);
-hipError_t launch_ln_modulate(int bf16, const float* x, const float* shift, const float* scale, void* out,
+hipError_t launch_ln_modulate(int bf16, float* x, const void* y, const float* shift, const float* scale, void* out,
                               int rows, int D, float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off,
                               hipStream_t s);
 hipError_t launch_cfg_ddim(float* x, const float* eps_c, const float* eps_u, float* eps_out, size_t n,

@@ -1,6 +1,6 @@
 // HBM-bound kernels of the denoising step: dtype conversion, timestep sinusoid,
 // batched GEMV (timestep MLP and adaLN modulation vectors), patch embedding,
-// LayerNorm + modulate, and the fused guidance + DDIM latent update.
+// residual add + LayerNorm + modulate, and the fused guidance + DDIM latent update.
 #include "common.h"
 
 namespace fc {
@@ -207,66 +207,105 @@ hipError_t launch_patch_embed(const float* latent, int R, int B, const float* Wp
   return hipGetLastError();
 }
 
-// ---------------------------------------------------------------- LayerNorm + modulate
-// One wave per row: the row is staged in LDS, mean and centred variance are wave
-// reductions (two passes over LDS, never over HBM), then
-// out = (x - mean) * rsqrt(var + eps) * (1 + scale) + shift.
-// Output row r (0..rows) reads input row (r / out_rows_per_b) * in_rows_per_b +
-// in_row_off + r % out_rows_per_b, which lets the final layer skip text rows.
-template <typename T>
-__global__ void k_ln_modulate(const float* __restrict__ x, const float* __restrict__ shift,
-                              const float* __restrict__ scale, T* __restrict__ out, int rows, int D, float eps,
-                              int in_rows_per_b, int out_rows_per_b, int in_row_off) {
-  extern __shared__ float s_row[];      // [waves][D]
+// ---------------------------------------------------------------- residual add + LayerNorm + modulate
+// One wave per row, the row held in registers (NCH 16-byte chunks per lane, all loads
+// issued before the first use).  If `y` is given, the pending branch output of the
+// previous linear layer is folded in first: x <- x + y (written back, fp32), then
+//   out = (x - mean) * rsqrt(var + eps) * (1 + scale) + shift
+// with mean and centred variance as wave reductions (two passes over registers).
+// Output row r reads input row (r / out_rows_per_b) * in_rows_per_b + in_row_off +
+// r % out_rows_per_b, which lets the output head skip text rows.
+template <typename T, int NCH>
+__global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, const T* __restrict__ y,
+                                                     const float* __restrict__ shift, const float* __restrict__ scale,
+                                                     T* __restrict__ out, int rows, int D, float eps, int in_rows_per_b,
+                                                     int out_rows_per_b, int in_row_off) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = blockIdx.x * (blockDim.x >> 6) + wave;
   if (r >= rows) return;
   const size_t in_r = (size_t)(r / out_rows_per_b) * in_rows_per_b + in_row_off + (r % out_rows_per_b);
-  const float* xr = x + in_r * D;
-  float* sr = s_row + (size_t)wave * D;
-  float sum = 0.0f;
-  for (int c = lane * 4; c < D; c += 256) {
-    f32x4 v = *(const f32x4*)(xr + c);
-    *(f32x4*)(sr + c) = v;
-    sum += (v[0] + v[1]) + (v[2] + v[3]);
+  float* xr = x + in_r * D;
+  f32x4 v[NCH];
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int c = lane * 4 + j * 256;
+    v[j] = c < D ? *(const f32x4*)(xr + c) : f32x4{0, 0, 0, 0};
   }
+  if (y) {
+    const T* yr = y + in_r * D;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      const int c = lane * 4 + j * 256;
+      if (c < D) {
+        if constexpr (sizeof(T) == 2) {
+          bf16x4 yv = *(const bf16x4*)(yr + c);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[j][e] += (float)yv[e];
+        } else {
+          v[j] += *(const f32x4*)(yr + c);
+        }
+        *(f32x4*)(xr + c) = v[j];
+      }
+    }
+  }
+  float sum = 0.0f;
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) sum += (v[j][0] + v[j][1]) + (v[j][2] + v[j][3]);
   const float mean = wave_sum(sum) / (float)D;
   float sq = 0.0f;
-  for (int c = lane * 4; c < D; c += 256) {
-    f32x4 v = *(const f32x4*)(sr + c) - mean;
-    sq += (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
+#pragma unroll
+  for (int j = 0; j < NCH; ++j) {
+    const int c = lane * 4 + j * 256;
+    if (c < D) {
+      f32x4 d = v[j] - mean;
+      sq += (d[0] * d[0] + d[1] * d[1]) + (d[2] * d[2] + d[3] * d[3]);
+    }
   }
   const float rstd = 1.0f / sqrtf(wave_sum(sq) / (float)D + eps);
   T* o = out + (size_t)r * D;
-  for (int c = lane * 4; c < D; c += 256) {
-    f32x4 v = (*(const f32x4*)(sr + c) - mean) * rstd;
-    if (scale) {
-      f32x4 sc = *(const f32x4*)(scale + c), sh = *(const f32x4*)(shift + c);
-      v = v * (1.0f + sc) + sh;
-    }
-    if constexpr (sizeof(T) == 2) {
-      bf16x4 ov;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)v[e];
-      *(bf16x4*)(o + c) = ov;
-    } else {
-      *(f32x4*)(o + c) = v;
+  for (int j = 0; j < NCH; ++j) {
+    const int c = lane * 4 + j * 256;
+    if (c < D) {
+      f32x4 w = (v[j] - mean) * rstd;
+      if (scale) {
+        f32x4 sc = *(const f32x4*)(scale + c), sh = *(const f32x4*)(shift + c);
+        w = w * (1.0f + sc) + sh;
+      }
+      if constexpr (sizeof(T) == 2) {
+        bf16x4 ov;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)w[e];
+        *(bf16x4*)(o + c) = ov;
+      } else {
+        *(f32x4*)(o + c) = w;
+      }
     }
   }
 }
 
-hipError_t launch_ln_modulate(int bf16, const float* x, const float* shift, const float* scale, void* out,
+template <typename T>
+static hipError_t run_ln(float* x, const void* y, const float* shift, const float* scale, void* out, int rows, int D,
+                         float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off, hipStream_t s) {
+  dim3 grid(ceil_div(rows, 4));
+#define FC_LN(N)                                                                                                   \
+  k_ln_modulate<T, N><<<grid, 256, 0, s>>>(x, (const T*)y, shift, scale, (T*)out, rows, D, eps, in_rows_per_b,       \
+                                           out_rows_per_b, in_row_off)
+  if (D <= 256) FC_LN(1);
+  else if (D <= 1280) FC_LN(5);
+  else if (D <= 3072) FC_LN(12);
+  else if (D <= 4096) FC_LN(16);
+  else return hipErrorInvalidValue;
+#undef FC_LN
+  return hipGetLastError();
+}
+
+hipError_t launch_ln_modulate(int bf16, float* x, const void* y, const float* shift, const float* scale, void* out,
                               int rows, int D, float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off,
                               hipStream_t s) {
   if (rows == 0) return hipSuccess;
-  const int waves = 4;
-  size_t sh = (size_t)waves * D * sizeof(float);
-  dim3 grid(ceil_div(rows, waves));
-  if (bf16) k_ln_modulate<bf16_t><<<grid, waves * 64, sh, s>>>(x, shift, scale, (bf16_t*)out, rows, D, eps,
-                                                               in_rows_per_b, out_rows_per_b, in_row_off);
-  else k_ln_modulate<float><<<grid, waves * 64, sh, s>>>(x, shift, scale, (float*)out, rows, D, eps,
-                                                         in_rows_per_b, out_rows_per_b, in_row_off);
-  return hipGetLastError();
+  if (bf16) return run_ln<bf16_t>(x, y, shift, scale, out, rows, D, eps, in_rows_per_b, out_rows_per_b, in_row_off, s);
+  return run_ln<float>(x, y, shift, scale, out, rows, D, eps, in_rows_per_b, out_rows_per_b, in_row_off, s);
 }
 
 // ---------------------------------------------------------------- guidance + DDIM update

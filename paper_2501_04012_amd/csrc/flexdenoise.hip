@@ -261,6 +261,9 @@ struct Ctx {
   Workspace w;
   int R, use_cfg;
   hipStream_t s;
+  // A branch's gated output sits in w.q, not yet added to the residual stream: the next
+  // LayerNorm launch folds it in (x <- x + y) while it has the row in registers.
+  mutable bool pending = false;
 };
 
 struct ProfScope {        // records an event pair around the launches made in its lifetime
@@ -331,9 +334,19 @@ int prepare(const Ctx& c, const float* cond, const float* null_cond) {
 int ln_mod(const Ctx& c, const float* shift, const float* scale) {
   const fc_model* m = c.m;
   ProfScope ps(c, PC_LN_MODULATE);
-  HIP_TRY(launch_ln_modulate(m->bf16, c.w.x, shift, scale, c.w.u, c.w.B * m->Ns, m->cfg.hidden, m->cfg.ln_eps,
-                             m->Ns, m->Ns, 0, c.s));
+  HIP_TRY(launch_ln_modulate(m->bf16, c.w.x, c.pending ? c.w.q : nullptr, shift, scale, c.w.u, c.w.B * m->Ns,
+                             m->cfg.hidden, m->cfg.ln_eps, m->Ns, m->Ns, 0, c.s));
+  c.pending = false;
   return FC_OK;
+}
+
+// Branch output projection: y = gate * (A W + b) into w.q (q, k, v are dead by then).
+int branch_out(const Ctx& c, int cat, const void* A, const Linear& L, const float* gate) {
+  EpiParams ep;
+  ep.out = c.w.q; ep.ldo = c.m->cfg.hidden; ep.gate = gate;
+  int rc = linear(c, cat, EPI_GATE, A, L, c.w.B * c.m->Ns, ep);
+  c.pending = rc == FC_OK;
+  return rc;
 }
 
 // Self-attention branch: x += gate * proj(attn(qkv(u))).  mode 0 spatial, 1 temporal, 2 all tokens.
@@ -357,9 +370,7 @@ int self_attention_branch(const Ctx& c, const Linear& qkv, const Linear& proj, c
     ProfScope ps(c, mode == 0 ? PC_ATTN_SPATIAL : mode == 1 ? PC_ATTN_TEMPORAL : PC_ATTN_FULL);
     HIP_TRY(launch_attention(m->bf16, ap, 0, c.s));
   }
-  EpiParams ep;
-  ep.x = w.x; ep.ldo = cf.hidden; ep.gate = gate;
-  return linear(c, PC_GEMM_PROJ, EPI_RESID, w.u, proj, rows, ep);
+  return branch_out(c, PC_GEMM_PROJ, w.u, proj, gate);
 }
 
 int cross_attention_branch(const Ctx& c, const Block& b, int layer) {
@@ -386,9 +397,7 @@ int cross_attention_branch(const Ctx& c, const Block& b, int layer) {
     ProfScope ps(c, PC_ATTN_CROSS);
     HIP_TRY(launch_attention(m->bf16, ap, 0, c.s));
   }
-  EpiParams ep;
-  ep.x = w.x; ep.ldo = cf.hidden; ep.gate = nullptr;
-  return linear(c, PC_GEMM_PROJ, EPI_RESID, w.u, b.xproj, rows, ep);
+  return branch_out(c, PC_GEMM_PROJ, w.u, b.xproj, nullptr);
 }
 
 int mlp_branch(const Ctx& c, const Block& b, const float* mod) {
@@ -400,9 +409,7 @@ int mlp_branch(const Ctx& c, const Block& b, const float* mod) {
   e1.out = c.w.hid; e1.ldo = m->cfg.mlp_dim;
   rc = linear(c, PC_GEMM_FC1, EPI_GELU, c.w.u, b.fc1, rows, e1);
   if (rc != FC_OK) return rc;
-  EpiParams e2;
-  e2.x = c.w.x; e2.ldo = D; e2.gate = mod + 2 * D;
-  return linear(c, PC_GEMM_FC2, EPI_RESID, c.w.hid, b.fc2, rows, e2);
+  return branch_out(c, PC_GEMM_FC2, c.w.hid, b.fc2, mod + 2 * D);
 }
 
 // One forward pass of all B rows + guidance + DDIM update of the R latents.
@@ -459,8 +466,9 @@ int run_step(const Ctx& c, float* latent, const fc_schedule* sched, int step, fl
   // head: LN + modulate on the video rows, Linear D -> p*p*C, scatter back to latent layout
   {
   ProfScope ps(c, PC_LN_MODULATE);
-  HIP_TRY(launch_ln_modulate(m->bf16, w.x, w.fmod, w.fmod + D, w.u, w.B * m->N, D, cf.ln_eps, m->Ns, m->N,
-                             text_rows, c.s));
+  HIP_TRY(launch_ln_modulate(m->bf16, w.x, c.pending ? w.q : nullptr, w.fmod, w.fmod + D, w.u, w.B * m->N, D,
+                             cf.ln_eps, m->Ns, m->N, text_rows, c.s));
+  c.pending = false;
   }
   EpiParams ep;
   ep.eps = w.eps; ep.T = cf.frames; ep.H = cf.height; ep.W = cf.width; ep.C = cf.channels; ep.p = cf.patch;
@@ -502,7 +510,8 @@ int fc_model_create(const fc_model_config* cfg, fc_model** out) {
     return fail(FC_ERR_SHAPE, "non-positive dimension");
   if (c.height % c.patch || c.width % c.patch) return fail(FC_ERR_SHAPE, "height/width not divisible by patch");
   if (c.hidden % c.heads) return fail(FC_ERR_SHAPE, "hidden not divisible by heads");
-  if (c.hidden % 4 || c.t_embed_dim % 2) return fail(FC_ERR_SHAPE, "hidden must be a multiple of 4, t_embed_dim even");
+  if (c.hidden % 4 || c.hidden > 4096 || c.t_embed_dim % 2)
+    return fail(FC_ERR_SHAPE, "hidden must be a multiple of 4, at most 4096; t_embed_dim even");
   if (c.attn_mode != FC_ATTN_FACTORIZED_CROSS && c.attn_mode != FC_ATTN_FULL3D_CONCAT)
     return fail(FC_ERR_SHAPE, "unknown attn_mode");
   if (c.dtype != FC_F32 && c.dtype != FC_BF16) return fail(FC_ERR_SHAPE, "unknown dtype");
@@ -708,23 +717,14 @@ int fc_profile_read(fc_model* m, int32_t n, double* ms_out, int64_t* launches_ou
 }
 
 // ---------------------------------------------------------------- single operators
-int fc_op_linear(int32_t dtype, const void* A, const void* Wt, const float* bias, void* out, int32_t M, int32_t N,
-                 int32_t K, int32_t epilogue, void* stream) {
+int fc_op_linear(int32_t dtype, const void* A, const void* Wt, const float* bias, const float* gate, void* out,
+                 int32_t M, int32_t N, int32_t K, int32_t epilogue, void* stream) {
   if (!A || !Wt || !out) return fail(FC_ERR_NULL, "NULL argument");
-  if (M < 0 || N < 0 || K < 0 || (epilogue != 0 && epilogue != 1)) return fail(FC_ERR_RANGE, "bad size or epilogue");
+  if (M < 0 || N < 0 || K < 0 || epilogue < 0 || epilogue > 2) return fail(FC_ERR_RANGE, "bad size or epilogue");
   EpiParams ep;
-  ep.bias = bias; ep.out = out; ep.ldo = N;
-  HIP_TRY(launch_gemm(dtype == FC_BF16, epilogue ? EPI_GELU : EPI_STORE, A, Wt, M, N, K, ep, (hipStream_t)stream));
-  return FC_OK;
-}
-
-int fc_op_linear_residual(int32_t dtype, const void* A, const void* Wt, const float* bias, const float* gate,
-                          float* x, int32_t M, int32_t N, int32_t K, void* stream) {
-  if (!A || !Wt || !x) return fail(FC_ERR_NULL, "NULL argument");
-  if (M < 0 || N < 0 || K < 0) return fail(FC_ERR_RANGE, "bad size");
-  EpiParams ep;
-  ep.bias = bias; ep.x = x; ep.ldo = N; ep.gate = gate;
-  HIP_TRY(launch_gemm(dtype == FC_BF16, EPI_RESID, A, Wt, M, N, K, ep, (hipStream_t)stream));
+  ep.bias = bias; ep.out = out; ep.ldo = N; ep.gate = gate;
+  const int mode = epilogue == 0 ? EPI_STORE : epilogue == 1 ? EPI_GELU : EPI_GATE;
+  HIP_TRY(launch_gemm(dtype == FC_BF16, mode, A, Wt, M, N, K, ep, (hipStream_t)stream));
   return FC_OK;
 }
 
@@ -745,12 +745,12 @@ int fc_op_attention(int32_t dtype, const void* q, const void* k, const void* v, 
   return FC_OK;
 }
 
-int fc_op_layernorm_modulate(int32_t dtype, const float* x, const float* shift, const float* scale, void* out,
-                             int32_t M, int32_t D, float eps, void* stream) {
+int fc_op_layernorm_modulate(int32_t dtype, float* x, const void* y, const float* shift, const float* scale,
+                             void* out, int32_t M, int32_t D, float eps, void* stream) {
   if (!x || !out) return fail(FC_ERR_NULL, "NULL argument");
   if ((shift == nullptr) != (scale == nullptr)) return fail(FC_ERR_NULL, "shift and scale go together");
-  if (M < 0 || D < 4 || D % 4) return fail(FC_ERR_RANGE, "D must be a positive multiple of 4");
-  HIP_TRY(launch_ln_modulate(dtype == FC_BF16, x, shift, scale, out, M, D, eps, M > 0 ? M : 1, M > 0 ? M : 1, 0,
+  if (M < 0 || D < 4 || D % 4 || D > 4096) return fail(FC_ERR_RANGE, "D must be a multiple of 4 in 4..4096");
+  HIP_TRY(launch_ln_modulate(dtype == FC_BF16, x, y, shift, scale, out, M, D, eps, M > 0 ? M : 1, M > 0 ? M : 1, 0,
                              (hipStream_t)stream));
   return FC_OK;
 }

@@ -250,7 +250,7 @@ hipError_t launch_gemm(int bf16, int mode, const void* A, const void* Wt, int M,
   switch (mode) {
     case EPI_STORE: return dispatch_mode<EPI_STORE>(bf16, A, Wt, M, N, K, ep, s);
     case EPI_GELU: return dispatch_mode<EPI_GELU>(bf16, A, Wt, M, N, K, ep, s);
-    case EPI_RESID: return dispatch_mode<EPI_RESID>(bf16, A, Wt, M, N, K, ep, s);
+    case EPI_GATE: return dispatch_mode<EPI_GATE>(bf16, A, Wt, M, N, K, ep, s);
     case EPI_HEADS: return dispatch_mode<EPI_HEADS>(bf16, A, Wt, M, N, K, ep, s);
     case EPI_UNPATCH: return dispatch_mode<EPI_UNPATCH>(bf16, A, Wt, M, N, K, ep, s);
   }

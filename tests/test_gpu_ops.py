@@ -39,7 +39,7 @@ def test_linear_bf16(fc, M, N, K, epilogue):
     if epilogue:
         want = dit.gelu_tanh(want)
     out = torch.empty((M, N), dtype=torch.bfloat16, device="cuda:0")
-    fc.fc_op_linear(fc.FC_BF16, dev(A, True), dev(W.T.copy(), True), dev(b), out, M, N, K, epilogue)
+    fc.fc_op_linear(fc.FC_BF16, dev(A, True), dev(W.T.copy(), True), dev(b), None, out, M, N, K, epilogue)
     torch.cuda.synchronize()
     got = host(out)
     assert rel_l2(got, want) < 4e-3, (rel_l2(got, want), max_abs(got, want))
@@ -54,7 +54,7 @@ def test_linear_fp32(fc, M, N, K):
     W = rng.standard_normal((K, N), dtype=np.float32)
     b = rng.standard_normal(N, dtype=np.float32)
     out = torch.empty((M, N), dtype=torch.float32, device="cuda:0")
-    fc.fc_op_linear(fc.FC_F32, dev(A), dev(W.T.copy()), dev(b), out, M, N, K, 1)
+    fc.fc_op_linear(fc.FC_F32, dev(A), dev(W.T.copy()), dev(b), None, out, M, N, K, 1)
     torch.cuda.synchronize()
     want = dit.gelu_tanh(A.astype(np.float64) @ W.astype(np.float64) + b)
     assert rel_l2(host(out), want) < 1e-5
@@ -62,7 +62,9 @@ def test_linear_fp32(fc, M, N, K):
 
 @pytest.mark.parametrize("dtype", ["bf16", "f32"])
 @pytest.mark.parametrize("gated", [True, False])
-def test_linear_residual(fc, dtype, gated):
+def test_linear_gated_branch_then_residual_layernorm(fc, dtype, gated):
+    """The gated branch output (epilogue 2) and the LayerNorm that folds it into the
+    residual stream, against x + gate * (A W + b) and LayerNorm of that."""
     torch = _torch()
     M, N, K = 333, 192, 128
     rng = np.random.default_rng(5)
@@ -74,12 +76,20 @@ def test_linear_residual(fc, dtype, gated):
     b = rng.standard_normal(N, dtype=np.float32)
     g = rng.standard_normal(N, dtype=np.float32) if gated else None
     x = rng.standard_normal((M, N), dtype=np.float32)
-    want = x + (g if gated else 1.0) * (A.astype(np.float64) @ W.astype(np.float64) + b)
-    dx = dev(x)
-    fc.fc_op_linear_residual(fc.FC_BF16 if bf else fc.FC_F32, dev(A, bf), dev(W.T.copy(), bf), dev(b),
-                             dev(g) if gated else None, dx, M, N, K)
+    sh, sc = rng.standard_normal(N, dtype=np.float32), rng.standard_normal(N, dtype=np.float32)
+    branch = (g if gated else 1.0) * (A.astype(np.float64) @ W.astype(np.float64) + b)
+    want_x = x + branch
+    want_u = dit.modulate(dit.layernorm(want_x, 1e-6), sh, sc)
+    code = fc.FC_BF16 if bf else fc.FC_F32
+    tdt = torch.bfloat16 if bf else torch.float32
+    y = torch.empty((M, N), dtype=tdt, device="cuda:0")
+    fc.fc_op_linear(code, dev(A, bf), dev(W.T.copy(), bf), dev(b), dev(g) if gated else None, y, M, N, K, 2)
+    dx, u = dev(x), torch.empty((M, N), dtype=tdt, device="cuda:0")
+    fc.fc_op_layernorm_modulate(code, dx, y, dev(sh), dev(sc), u, M, N, 1e-6)
     torch.cuda.synchronize()
-    assert rel_l2(host(dx), want) < (1e-5 if not bf else 1e-5)   # fp32 accumulate, fp32 output in both
+    assert rel_l2(host(y), branch) < (4e-3 if bf else 1e-5)
+    assert rel_l2(host(dx), want_x) < (3e-3 if bf else 1e-5)      # bf16: the branch is rounded before the add
+    assert rel_l2(host(u), want_u) < (6e-3 if bf else 1e-5)
 
 
 # --------------------------------------------------------------------------- attention
@@ -142,7 +152,7 @@ def test_attention_rows_are_convex_combinations(fc):
 
 # --------------------------------------------------------------------------- LayerNorm + modulate
 
-@pytest.mark.parametrize("M,D", [(1, 64), (37, 1152), (130, 3072), (5, 4)])
+@pytest.mark.parametrize("M,D", [(1, 64), (37, 1152), (130, 3072), (5, 4), (9, 4096), (3, 260)])
 @pytest.mark.parametrize("bf", [False, True])
 @pytest.mark.parametrize("mod", [True, False])
 def test_layernorm_modulate(fc, M, D, bf, mod):
@@ -155,10 +165,12 @@ def test_layernorm_modulate(fc, M, D, bf, mod):
     if mod:
         want = dit.modulate(want, sh, sc)
     out = torch.empty((M, D), dtype=torch.bfloat16 if bf else torch.float32, device="cuda:0")
-    fc.fc_op_layernorm_modulate(fc.FC_BF16 if bf else fc.FC_F32, dev(x), dev(sh) if mod else None,
+    dx = dev(x)
+    fc.fc_op_layernorm_modulate(fc.FC_BF16 if bf else fc.FC_F32, dx, None, dev(sh) if mod else None,
                                 dev(sc) if mod else None, out, M, D, 1e-6)
     torch.cuda.synchronize()
     assert rel_l2(host(out), want) < (4e-3 if bf else 2e-6)
+    assert np.array_equal(host(dx), x)                        # no pending branch: x untouched
 
 
 # --------------------------------------------------------------------------- guidance + DDIM
