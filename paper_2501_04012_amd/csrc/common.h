@@ -48,7 +48,8 @@ inline size_t round_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
 // ---------------------------------------------------------------- GEMM epilogues
 // Every GEMM kernel hands its accumulators to an epilogue as groups of four
 // consecutive rows (m0..m0+3) of one column n, the natural unit of the 32x32 MFMA
-// accumulator layout.  `Mvalid` bounds rows, `Nvalid` bounds columns.
+// accumulator layout.  `Mvalid` bounds rows, `Nvalid` bounds columns.  Column-only
+// quantities (bias, gate, head and patch decomposition) are hoisted into a `Col`.
 
 enum EpiMode : int {
   EPI_STORE = 0,     // out[m,n] = acc + bias
@@ -75,55 +76,91 @@ struct EpiParams {
   int T = 0, H = 0, W = 0, C = 0, p = 0;
 };
 
+// Division of a row index by a runtime constant without an integer divide:
+// q = (m * mul) >> 40 with mul = ceil(2^40 / d) is exact while m * d < 2^40.
+struct FastDiv {
+  unsigned long long mul = 0;
+  unsigned d = 1;
+  FastDiv() = default;
+  explicit FastDiv(unsigned div) : mul(((1ull << 40) + div - 1) / div), d(div) {}
+  __device__ __forceinline__ unsigned div(unsigned m) const { return (unsigned)(((unsigned long long)m * mul) >> 40); }
+};
+
 template <typename T, int MODE>
 struct Epilogue {
   EpiParams P;
   int Mvalid, Nvalid;
+  FastDiv rows_per_b;          // EPI_HEADS: tokens;  EPI_UNPATCH: T*S
+  FastDiv unp_S, unp_gw;       // EPI_UNPATCH
 
-  __device__ __forceinline__ void store4(int m0, int n, const float (&acc)[4]) const {
-    if (n >= Nvalid || m0 >= Mvalid) return;
-    const float b = P.bias ? P.bias[n] : 0.0f;
+  // host side: fills the divisors the mode needs
+  static Epilogue make(const EpiParams& p, int M, int N) {
+    Epilogue e{p, M, N, FastDiv(), FastDiv(), FastDiv()};
+    if (MODE == EPI_HEADS) e.rows_per_b = FastDiv((unsigned)p.tokens);
+    if (MODE == EPI_UNPATCH) {
+      const int gw = p.W / p.p, S = gw * (p.H / p.p);
+      e.rows_per_b = FastDiv((unsigned)(p.T * S));
+      e.unp_S = FastDiv((unsigned)S);
+      e.unp_gw = FastDiv((unsigned)gw);
+    }
+    return e;
+  }
+
+  // Everything that depends on the output column only, computed once per column.
+  struct Col {
+    float bias, mul;           // mul: gate (EPI_GATE) or q scale (EPI_HEADS)
+    T* base;                   // column base pointer (EPI_UNPATCH: nullptr, see foff)
+    size_t foff;               // EPI_UNPATCH: offset of (dh, dw, c) inside a patch origin
+    bool valid;
+  };
+
+  __device__ __forceinline__ Col col(int n) const {
+    Col c;
+    c.valid = n < Nvalid;
+    const int nn = c.valid ? n : 0;
+    c.bias = P.bias ? P.bias[nn] : 0.0f;
+    c.mul = 1.0f;
+    c.base = nullptr;
+    c.foff = 0;
     if constexpr (MODE == EPI_STORE || MODE == EPI_GELU || MODE == EPI_GATE) {
-      T* o = (T*)P.out;
-      float g = 1.0f;
-      if constexpr (MODE == EPI_GATE) g = P.gate ? P.gate[n] : 1.0f;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        if (m0 + e < Mvalid) {
-          float v = acc[e] + b;
-          if constexpr (MODE == EPI_GELU) v = gelu_tanh_f(v);
-          if constexpr (MODE == EPI_GATE) v *= g;
-          o[(size_t)(m0 + e) * P.ldo + n] = from_f32<T>(v);
-        }
-      }
+      c.base = (T*)P.out + nn;
+      if constexpr (MODE == EPI_GATE) c.mul = P.gate ? P.gate[nn] : 1.0f;
     } else if constexpr (MODE == EPI_HEADS) {
-      const int which = P.which0 + n / P.D;
-      const int c = n % P.D;
-      const int head = c / P.hd, dd = c % P.hd;
-      T* dst = (T*)(which == 0 ? P.q : which == 1 ? P.k : P.v);
-      const float sc = which == 0 ? P.qscale : 1.0f;
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        int m = m0 + e;
-        if (m < Mvalid) {
-          int bb = m / P.tokens, tok = m % P.tokens;
-          dst[(((size_t)bb * P.heads + head) * P.tokens + tok) * P.hd + dd] = from_f32<T>((acc[e] + b) * sc);
-        }
-      }
+      const int which = P.which0 + nn / P.D;
+      const int cc = nn % P.D;
+      const int head = cc / P.hd, dd = cc % P.hd;
+      c.base = (T*)(which == 0 ? P.q : which == 1 ? P.k : P.v) + (size_t)head * P.tokens * P.hd + dd;
+      c.mul = which == 0 ? P.qscale : 1.0f;
     } else if constexpr (MODE == EPI_UNPATCH) {
-      const int gw = P.W / P.p, gh = P.H / P.p;
-      const int S = gw * gh;
-      const int dh = n / (P.p * P.C), dw = (n / P.C) % P.p, c = n % P.C;
+      const int dh = nn / (P.p * P.C), dw = (nn / P.C) % P.p, ch = nn % P.C;
+      c.foff = ((size_t)dh * P.W + dw) * P.C + ch;
+    }
+    return c;
+  }
+
+  // Four consecutive rows m0..m0+3 of column c (the unit of the 32x32 MFMA accumulator).
+  __device__ __forceinline__ void store4(const Col& c, int m0, const float (&acc)[4]) const {
+    if (!c.valid || m0 >= Mvalid) return;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        int m = m0 + e;
-        if (m < Mvalid) {
-          int bb = m / (P.T * S), r = m % (P.T * S);
-          int t = r / S, s = r % S;
-          int hp = s / gw, wp = s % gw;
-          size_t idx = ((((size_t)bb * P.T + t) * P.H + hp * P.p + dh) * P.W + wp * P.p + dw) * P.C + c;
-          P.eps[idx] = acc[e] + b;
-        }
+    for (int e = 0; e < 4; ++e) {
+      const int m = m0 + e;
+      if (m >= Mvalid) break;
+      float v = acc[e] + c.bias;
+      if constexpr (MODE == EPI_GELU) v = gelu_tanh_f(v);
+      if constexpr (MODE == EPI_GATE || MODE == EPI_HEADS) v *= c.mul;
+      if constexpr (MODE == EPI_STORE || MODE == EPI_GELU || MODE == EPI_GATE) {
+        c.base[(size_t)m * P.ldo] = from_f32<T>(v);
+      } else if constexpr (MODE == EPI_HEADS) {
+        // row (bb, tok) of [b, head, tok, hd]: offset (m + bb*(heads-1)*tokens) * hd
+        const unsigned bb = rows_per_b.div((unsigned)m);
+        c.base[((size_t)m + (size_t)bb * (P.heads - 1) * P.tokens) * P.hd] = from_f32<T>(v);
+      } else if constexpr (MODE == EPI_UNPATCH) {
+        const unsigned bb = rows_per_b.div((unsigned)m);
+        const unsigned r = (unsigned)m - bb * rows_per_b.d;
+        const unsigned t = unp_S.div(r), sidx = r - t * unp_S.d;
+        const unsigned hp = unp_gw.div(sidx), wp = sidx - hp * unp_gw.d;
+        const size_t origin = ((((size_t)bb * P.T + t) * P.H + hp * P.p) * P.W + wp * P.p) * P.C;
+        P.eps[origin + c.foff] = v;
       }
     }
   }

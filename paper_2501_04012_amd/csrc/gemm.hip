@@ -149,12 +149,12 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j) {
-      const int n = bn0 + wc * WTN + j * 32 + li;
+      const auto col = epi.col(bn0 + wc * WTN + j * 32 + li);
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         const int m0 = bm0 + wr * WTM + i * 32 + g * 8 + lh * 4;
         float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-        epi.store4(m0, n, v);
+        epi.store4(col, m0, v);
       }
     }
 }
@@ -195,7 +195,7 @@ __global__ __launch_bounds__(256) void k_gemm_plain(const T* __restrict__ A, con
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     float v[4] = {acc[0][j], acc[1][j], acc[2][j], acc[3][j]};
-    epi.store4(bm0 + tr * 4, bn0 + tc * 4 + j, v);
+    epi.store4(epi.col(bn0 + tc * 4 + j), bm0 + tr * 4, v);
   }
 }
 
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(256) void k_gemm_plain(const T* __restrict__ A, con
 template <int BM, int BN, int BK, int WR, int WC, int S, int MODE>
 static hipError_t run_dlds(const void* A, const void* Wt, int M, int N, int K, const EpiParams& ep, hipStream_t s) {
   using Epi = Epilogue<bf16_t, MODE>;
-  Epi epi{ep, M, N};
+  Epi epi = Epi::make(ep, M, N);
   constexpr size_t smem = (size_t)S * (BM + BN) * BK * sizeof(bf16_t);
   auto kern = k_gemm_dlds<BM, BN, BK, WR, WC, S, Epi>;
   static bool attr_set = false;
@@ -222,7 +222,7 @@ static hipError_t run_dlds(const void* A, const void* Wt, int M, int N, int K, c
 template <typename T, int MODE>
 static hipError_t run_plain(const void* A, const void* Wt, int M, int N, int K, const EpiParams& ep, hipStream_t s) {
   using Epi = Epilogue<T, MODE>;
-  Epi epi{ep, M, N};
+  Epi epi = Epi::make(ep, M, N);
   dim3 grid(ceil_div(N, 64), ceil_div(M, 64));
   k_gemm_plain<T, Epi><<<grid, 256, 0, s>>>((const T*)A, (const T*)Wt, M, N, K, epi);
   return hipGetLastError();
