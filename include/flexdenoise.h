@@ -175,8 +175,7 @@ int fc_op_linear(int32_t dtype, const void* A, const void* Wt, const float* bias
 
 /* Unmasked softmax(q k^T / sqrt(d)) v for G independent problems (one per
  * sequence and head).  q [G, nq, d], k [G, nk, d], v [G, nk, d], out [G, nq, d]
- * (all act).  impl 0: library's choice, 1: force the plain (non-MFMA) kernel,
- * 2: force the 8-wave ping-pong MFMA kernel where it applies (bf16, d = 64). */
+ * (all act).  impl 0: library's choice, 1: force the plain (non-MFMA) kernel. */
 int fc_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* out,
                     int32_t G, int32_t nq, int32_t nk, int32_t d, int32_t impl, void* hip_stream);
 

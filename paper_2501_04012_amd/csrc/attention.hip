@@ -565,327 +565,6 @@ static hipError_t run_flash(const AttnParams& p, hipStream_t s) {
   return hipGetLastError();
 }
 
-// ---------------------------------------------------------------- ping-pong flash kernel (head dim 64)
-// Same mathematics and MFMA layouts as k_attn_flash, restructured so that the matrix
-// pipe and the vector ALU work at the same time.  A workgroup has 8 waves: waves 0-3
-// (group A) and 4-7 (group B); wave w and wave w+4 share a SIMD.  Per key tile a wave
-// alternates between a vector phase (max, exp2, pack, row sum) and a matrix phase (P V
-// of this tile, then S of the next).  Group B runs the same loop one phase later, and a
-// workgroup barrier closes every phase, so whenever one wave of a SIMD issues MFMAs
-// the other issues the softmax of its own tile.
-//
-//   phase     group A                      group B
-//   -1        S(0)                         -
-//   2j        softmax(j)                   P V(j-1), S(j)
-//   2j+1      P V(j), S(j+1)               softmax(j)
-//   2J        -                            P V(J-1)
-//
-// K and V tiles ([64 keys][64 dims] each) travel global -> LDS by DMA
-// (global_load_lds_dwordx4) into a ring of 4 stages, two tiles ahead: the loads of tile
-// j+2 are issued at the start of phase 2j (its stage held tile j-2, last read in phase
-// 2j-2) and awaited before the barrier that closes phase 2j+2.  Rows are unpadded and
-// XOR-swizzled by 16-byte chunk so that both the ds_read_b128 of K fragments and the
-// transpose reads of V are free of bank conflicts; the swizzle is applied on the global
-// side because the DMA fixes where each lane's 16 bytes land.
-//   K: chunk kc of row r -> line r/2, slot (r&1)*8 + (kc ^ ((r/2)&7))
-//   V: chunk kc of row r -> line r/2, slot (r&1)*8 + 2*((kc/2) ^ ((r/2)&3)) + (kc&1)
-namespace pp {
-constexpr int HD = 64, NS = 4, STAGE = 16384, VOFF = 8192;
-typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((address_space(1))) const void gbl_void;
-template <int N> __device__ __forceinline__ void wait_vm() {
-  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
-}
-__device__ __forceinline__ int k_off(int r, int kc) { return (r >> 1) * 256 + (((r & 1) << 3) + (kc ^ ((r >> 1) & 7))) * 16; }
-__device__ __forceinline__ int v_off(int r, int kc) {
-  return (r >> 1) * 256 + (((r & 1) << 3) + ((((kc >> 1) ^ ((r >> 1) & 3)) << 1) | (kc & 1))) * 16;
-}
-}  // namespace pp
-
-__global__ __launch_bounds__(512, 2) void k_attn_pingpong(AttnParams p) {
-  using namespace pp;
-  extern __shared__ __attribute__((aligned(1024))) unsigned char smem_pp[];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int li = lane & 31, lh = lane >> 5;
-  const bool groupB = wave >= 4;
-
-  const int qtiles = (p.nq + 511) / 512;
-  const long long work = xcd_work_item((long long)p.B * p.heads * p.groups * qtiles);
-  if (work < 0) return;
-  int bid = (int)work;
-  const int qtile = bid % qtiles; bid /= qtiles;
-  const int g = bid % p.groups; bid /= p.groups;
-  const int head = bid % p.heads;
-  const int b = bid / p.heads;
-  const int kb = key_batch(p, b);
-
-  const bf16_t* qbase = (const bf16_t*)p.q + ((size_t)b * p.heads + head) * (size_t)p.q_tokens * HD;
-  const bf16_t* kbase = (const bf16_t*)p.k + (((size_t)kb * p.heads + head) * (size_t)p.k_tokens +
-                                              (size_t)g * p.k_gstride) * HD;
-  const bf16_t* vbase = (const bf16_t*)p.v + (((size_t)kb * p.heads + head) * (size_t)p.k_tokens +
-                                              (size_t)g * p.k_gstride) * HD;
-  const int nkt = (p.nk + 63) / 64;
-
-  // ---- DMA: wave w brings rows 8w..8w+7 of the K tile and of the V tile (1 KB each)
-  const int d_row = wave * 8 + ((lane >> 4) << 1) + ((lane & 15) >> 3);
-  const int d_kc_k = (lane & 7) ^ ((d_row >> 1) & 7);
-  const int d_kc_v = ((((lane & 7) >> 1) ^ ((d_row >> 1) & 3)) << 1) | (lane & 1);
-  auto issue = [&](int t) {
-    int j = t * 64 + d_row;
-    j = j < p.nk ? j : p.nk - 1;                     // keys past nk are masked in the softmax
-    unsigned char* st = smem_pp + (t % NS) * STAGE + wave * 1024;
-    __builtin_amdgcn_global_load_lds((gbl_void*)(kbase + (size_t)j * HD + d_kc_k * 8), (lds_void*)st, 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((gbl_void*)(vbase + (size_t)j * HD + d_kc_v * 8), (lds_void*)(st + VOFF), 16, 0,
-                                     0);
-  };
-  issue(0);
-  if (nkt > 1) issue(1);
-
-  // ---- Q fragments (B operand of the score MFMA), pre-multiplied by scale*log2(e)
-  bf16x8 qf[2][4];
-  const int q0 = qtile * 512 + wave * 64;
-#pragma unroll
-  for (int qt = 0; qt < 2; ++qt) {
-    int qi = q0 + qt * 32 + li;
-    qi = qi < p.nq ? qi : p.nq - 1;
-    const bf16_t* qr = qbase + (size_t)(g * p.q_gstride + qi) * HD;
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      bf16x8 v = *(const bf16x8*)(qr + s * 16 + lh * 8);
-      if (p.scale_log2 != 1.0f) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = (bf16_t)((float)v[e] * p.scale_log2);
-      }
-      qf[qt][s] = v;
-    }
-  }
-
-  f32x16 oacc[2][2], sacc[2][2], negm[2];
-#pragma unroll
-  for (int c = 0; c < 2; ++c)
-#pragma unroll
-    for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) { oacc[c][qt][r] = 0.0f; sacc[c][qt][r] = 0.0f; }
-#pragma unroll
-  for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) negm[qt][r] = 0.0f;
-  float lrow[2] = {0.0f, 0.0f};
-  bf16x8 pf[2][2][2];
-  bf16x2 ones;
-  ones[0] = (bf16_t)1.0f; ones[1] = (bf16_t)1.0f;
-  constexpr float kLazy = 8.0f;
-
-  // fragment addressing inside a stage
-  const int prow = (li & 0x13) | ((li & 4) << 1) | ((li & 8) >> 1);   // li with bits 2 and 3 swapped
-  const int tr_row = (lane & 15) >> 2;
-  const int tr_dim = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
-
-  // K fragment (row a*32 + prow, chunk 2s + h): a*4096 is an immediate, the swizzled chunk is
-  // one per-lane value per s.  V transpose read (row 32a + 16s2 + 8h + 4*half + tr_row, dims
-  // 32c + tr_dim): with y = tr_row/2 and x = lane bit 4, the swizzled chunk pair is
-  // 2(c^half) + (x^y), so everything but one per-lane base is an immediate.
-  int k_lane[4];
-#pragma unroll
-  for (int s = 0; s < 4; ++s) k_lane[s] = k_off(prow, 2 * s + lh);
-  const int v_lane = (4 * lh + (tr_row >> 1)) * 256 + (tr_row & 1) * 128 +
-                     ((((lane >> 4) & 1) ^ (tr_row >> 1)) << 5) + (((tr_dim >> 3) & 1) << 4) + (tr_dim & 7) * 2;
-
-  // Fragment reads run one MFMA group ahead of their use so that the LDS latency hides
-  // behind the previous group's MFMAs (the other wave of the SIMD is busy with its softmax
-  // and cannot fill the matrix pipe).
-  auto load_k = [&](const unsigned char* ks, int s, bf16x8 (&kf)[2]) {
-#pragma unroll
-    for (int a = 0; a < 2; ++a) kf[a] = *(const bf16x8*)(ks + k_lane[s] + a * 4096);
-  };
-  auto load_v = [&](const unsigned char* vs, int grp, bf16x8 (&vf)[2]) {
-    const int a = grp >> 1, s2 = grp & 1;
-#pragma unroll
-    for (int c = 0; c < 2; ++c) {
-      bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(vs + (16 * a + 8 * s2) * 256 + (c ^ 0) * 64));
-      bf16x4 hi =
-          __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(vs + (16 * a + 8 * s2 + 2) * 256 + (c ^ 1) * 64));
-      vf[c] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    }
-  };
-
-  auto do_S = [&](int t) {
-    const unsigned char* ks = smem_pp + (t % NS) * STAGE;
-    bf16x8 kf[2][2];
-    load_k(ks, 0, kf[0]);
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      if (s + 1 < 4) load_k(ks, s + 1, kf[(s + 1) & 1]);
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
-          sacc[a][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s & 1][a], qf[qt][s],
-                                                                s == 0 ? negm[qt] : sacc[a][qt], 0, 0, 0);
-    }
-  };
-
-  auto do_PV = [&](int t) {
-    const unsigned char* vs = smem_pp + (t % NS) * STAGE + VOFF + v_lane;
-    bf16x8 vf[2][2];
-    load_v(vs, 0, vf[0]);
-#pragma unroll
-    for (int grp = 0; grp < 4; ++grp) {
-      if (grp + 1 < 4) load_v(vs, grp + 1, vf[(grp + 1) & 1]);
-      const int a = grp >> 1, s2 = grp & 1;
-#pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
-          oacc[c][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[grp & 1][c], pf[qt][a][s2], oacc[c][qt], 0, 0, 0);
-    }
-  };
-
-  auto do_softmax = [&](int t) {
-    if (t == nkt - 1 && (p.nk & 63) != 0) {            // keys past nk: only in the last tile
-      const int rem = p.nk - t * 64;
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int gg = 0; gg < 4; ++gg)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            int key = 32 * a + 16 * (gg >> 1) + 8 * lh + 4 * (gg & 1) + e;
-            if (key >= rem) { sacc[a][0][4 * gg + e] = -INFINITY; sacc[a][1][4 * gg + e] = -INFINITY; }
-          }
-    }
-    float mx[2];
-#pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-      float v = sacc[0][qt][0];
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) v = fmaxf(v, sacc[a][qt][r]);
-      mx[qt] = fmaxf(v, __shfl_xor(v, 32, 64));
-    }
-    const bool first = t == 0;
-    if (__builtin_expect(__any(first || mx[0] > kLazy || mx[1] > kLazy), 0)) {
-#pragma unroll
-      for (int qt = 0; qt < 2; ++qt) {
-        const float delta = (first || mx[qt] > kLazy) ? mx[qt] : 0.0f;
-        const float alpha = first ? 0.0f : __builtin_amdgcn_exp2f(-delta);
-        lrow[qt] *= alpha;
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) oacc[c][qt][r] *= alpha;
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) sacc[a][qt][r] -= delta;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) negm[qt][r] -= delta;
-      }
-    }
-#pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-      float sum = lrow[qt];
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          u32x4 pw;
-#pragma unroll
-          for (int x = 0; x < 4; ++x) {
-            bf16x2 pr;
-            pr[0] = (bf16_t)__builtin_amdgcn_exp2f(sacc[a][qt][8 * s2 + 2 * x]);
-            pr[1] = (bf16_t)__builtin_amdgcn_exp2f(sacc[a][qt][8 * s2 + 2 * x + 1]);
-            sum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum, false);
-            pw[x] = __builtin_bit_cast(unsigned int, pr);
-          }
-          pf[qt][a][s2] = __builtin_bit_cast(bf16x8, pw);
-        }
-      lrow[qt] = sum;
-    }
-  };
-
-  // closes a phase; `await_tile`: the DMA of the tile issued one even phase ago must have
-  // landed (the two loads issued in this phase may stay in flight)
-  auto close_phase = [&](bool await_tile, bool issued_now) {
-    if (await_tile) {
-      if (issued_now) wait_vm<2>(); else wait_vm<0>();
-    }
-    __builtin_amdgcn_s_barrier();
-  };
-
-  // tile 0 must be in LDS before phase -1 (this also retires the Q loads)
-  wait_vm<0>();
-  __builtin_amdgcn_s_barrier();
-
-  if (!groupB) {
-    do_S(0);
-    __builtin_amdgcn_s_barrier();                               // phase -1
-    for (int j = 0; j < nkt; ++j) {
-      const bool more = j + 2 < nkt;
-      if (more) issue(j + 2);
-      do_softmax(j);
-      close_phase(j + 1 < nkt, more);                           // phase 2j
-      do_PV(j);
-      if (j + 1 < nkt) do_S(j + 1);
-      __builtin_amdgcn_s_barrier();                             // phase 2j+1
-    }
-    __builtin_amdgcn_s_barrier();                               // phase 2J
-  } else {
-    __builtin_amdgcn_s_barrier();                               // phase -1
-    for (int j = 0; j < nkt; ++j) {
-      const bool more = j + 2 < nkt;
-      if (more) issue(j + 2);
-      if (j > 0) do_PV(j - 1);
-      do_S(j);
-      close_phase(j + 1 < nkt, more);                           // phase 2j
-      do_softmax(j);
-      __builtin_amdgcn_s_barrier();                             // phase 2j+1
-    }
-    do_PV(nkt - 1);
-    __builtin_amdgcn_s_barrier();                               // phase 2J
-  }
-
-  // ---- finish: O / l, token-major
-  bf16_t* obase = (bf16_t*)p.out + (size_t)b * p.q_tokens * ((size_t)p.heads * HD) + (size_t)head * HD;
-#pragma unroll
-  for (int qt = 0; qt < 2; ++qt) {
-    const float ltot = lrow[qt] + __shfl_xor(lrow[qt], 32, 64);
-    const float inv = 1.0f / ltot;
-    const int qi = q0 + qt * 32 + li;
-    if (qi < p.nq) {
-      bf16_t* orow = obase + (size_t)(g * p.q_gstride + qi) * ((size_t)p.heads * HD);
-#pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int gg = 0; gg < 4; ++gg) {
-          bf16x4 ov;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)(oacc[c][qt][4 * gg + e] * inv);
-          *(bf16x4*)(orow + 32 * c + 8 * gg + 4 * lh) = ov;
-        }
-    }
-  }
-}
-
-static hipError_t run_pingpong(const AttnParams& p, hipStream_t s) {
-  constexpr size_t smem = (size_t)pp::NS * pp::STAGE;
-  static bool attr_set = false;
-  if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute((const void*)k_attn_pingpong, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)smem);
-    if (e != hipSuccess) return e;
-    attr_set = true;
-  }
-  long long blocks = (long long)p.B * p.heads * p.groups * ((p.nq + 511) / 512);
-  if (blocks == 0) return hipSuccess;
-  blocks = (blocks + 7) / 8 * 8;
-  k_attn_pingpong<<<(unsigned)blocks, 512, smem, s>>>(p);
-  return hipGetLastError();
-}
-
 // The flash kernel needs unit-stride tokens inside a group, 16-byte aligned rows
 // (head dim a multiple of 8 elements) and head dims it is instantiated for.
 static bool flash_ok(const AttnParams& p) {
@@ -900,9 +579,7 @@ hipError_t launch_attention(int bf16, const AttnParams& p, int impl, hipStream_t
   // every kernel reads rows with 16-byte loads
   if ((((uintptr_t)p.q | (uintptr_t)p.k | (uintptr_t)p.v | (uintptr_t)p.out) & 15) != 0) return hipErrorInvalidValue;
   if (!bf16) return dispatch_plain<float>(p, impl != 1, s);
-  if ((impl == 0 || impl == 2 || impl == 3) && flash_ok(p)) {
-    if (impl == 3 && p.hd == 64) return run_flash<64>(p, s);
-    if (impl == 2 && p.hd == 64) return run_pingpong(p, s);
+  if (impl == 0 && flash_ok(p)) {
     if (p.hd == 64) return run_flash<64>(p, s);
     if (p.hd == 72) return run_flash<72>(p, s);
   }

@@ -97,6 +97,55 @@ def test_cfg3a_bf16_stack_depth4_with_guidance(fc):
     check(*got, *want, bf16=True)
 
 
+def test_cfg3a_bf16_full_28_block_stack_with_guidance(fc):
+    """The full-size stacked configuration, one guided step, against the fp32 oracle."""
+    w = synth.WORKLOADS["cfg3a"]
+    W = synth.make_weights(w.model, w.weight_seed)
+    inputs = synth.workload_inputs(w)
+    got = run_step_gpu(fc, w, weights=W, inputs=inputs)
+    want = oracle_step(w, w.model, W, inputs, w.step, dtype=np.float32)
+    check(*got, *want, bf16=True)
+
+
+def test_cfg5a_resume_first_step_teacher_forced(fc):
+    """Cache-hit resume at full size (4 requests x guidance pair, 28 blocks): the first
+    remaining step after k = 10 and after k = 20, all requests on the GPU in one batch,
+    request 0 and request 3 checked against the fp32 oracle fed the same stored latents."""
+    w = synth.WORKLOADS["cfg5a"]
+    W = synth.make_weights(w.model, w.weight_seed)
+    lat, cond, null = synth.workload_inputs(w)
+    for k, r in ((10, 0), (20, 3)):
+        got_lat, got_eps = run_step_gpu(fc, w, step=k + 1, weights=W, inputs=(lat, cond, null))
+        want_lat, want_eps = sampler.denoise_step(w.model, W, lat[r:r + 1], cond[r:r + 1], null, w.schedule, k + 1,
+                                                  dtype=np.float32, return_eps=True)
+        check(got_lat[r:r + 1], got_eps[r:r + 1], want_lat, want_eps, bf16=True)
+
+
+def test_cfg5a_resume_runs_the_remaining_steps(fc):
+    """fc_denoise_resume at full size: k = 48 leaves two steps; it must equal two single
+    steps bit for bit (same kernels, same order), and k = N must leave the latent alone."""
+    import torch
+    w = synth.WORKLOADS["cfg5a"]
+    W = synth.make_weights(w.model, w.weight_seed)
+    lat, cond, null = synth.workload_inputs(w)
+    den = fc.Denoiser(w.model, W, w.requests, True)
+    try:
+        d_cond, d_null = dev(cond), dev(null)
+        a, b = dev(lat), dev(lat)
+        den.resume(a, d_cond, d_null, w.schedule, 48)
+        den.step(b, d_cond, d_null, w.schedule, 49)
+        den.step(b, d_cond, d_null, w.schedule, 50)
+        torch.cuda.synchronize()
+        assert torch.equal(a, b)
+        assert torch.isfinite(a).all()
+        c = dev(lat)
+        den.resume(c, d_cond, d_null, w.schedule, 50)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(c), lat)
+    finally:
+        den.close()
+
+
 def test_cfg5b_resume_trajectory_and_invariants(fc):
     import torch
     w = synth.WORKLOADS["cfg5b"]
