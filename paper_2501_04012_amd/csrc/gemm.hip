@@ -128,21 +128,43 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
     __builtin_amdgcn_s_barrier();
     if (kt + S - 1 < nkt) issue(kt + S - 1, (kt + S - 1) % S);
     const unsigned char* st = smem + (kt % S) * STAGE_BYTES;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[TM], fb[TN];
+    // Fragment reads run one 16-wide k-slice ahead of the MFMAs that consume them, in
+    // two register sets.  The scheduling groups below pin the instruction order the
+    // compiler would otherwise collapse into read-all / wait / multiply: after the first
+    // slice's reads, every read of slice ks+1 is paired with one MFMA of slice ks, so the
+    // LDS latency is spent under matrix work of the same wave.
+    constexpr int KS = BK / 16;
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto load = [&](int ks, bf16x8 (&xa)[TM], bf16x8 (&xb)[TN]) {
       const unsigned char* pa = st + a_row + (((2 * ks + lh) ^ a_x) << 4);
       const unsigned char* pb = st + b_row + (((2 * ks + lh) ^ b_x) << 4);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) fa[i] = *(const bf16x8*)(pa + i * TILE_STRIDE);
+      for (int i = 0; i < TM; ++i) xa[i] = *(const bf16x8*)(pa + i * TILE_STRIDE);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) fb[j] = *(const bf16x8*)(pb + j * TILE_STRIDE);
+      for (int j = 0; j < TN; ++j) xb[j] = *(const bf16x8*)(pb + j * TILE_STRIDE);
+    };
+    load(0, fa[0], fb[0]);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) load(ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
 #pragma unroll
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
     }
+    constexpr int kDsRead = 0x100, kMfma = 0x008;
+    __builtin_amdgcn_sched_group_barrier(kDsRead, TM + TN, 0);
+#pragma unroll
+    for (int ks = 0; ks + 1 < KS; ++ks) {
+#pragma unroll
+      for (int r = 0; r < TM + TN; ++r) {
+        __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);
+      }
+      if (TM * TN > TM + TN) __builtin_amdgcn_sched_group_barrier(kMfma, TM * TN - (TM + TN), 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(kMfma, TM * TN, 0);
   }
 
 #pragma unroll
