@@ -8,7 +8,7 @@ import pytest
 
 from oracle import dit, sampler
 from paper_2501_04012_amd import synth
-from util import dev, host, max_abs, rel_l2, run_step_gpu
+from util import dev, host, max_abs, record, rel_l2, run_step_gpu
 
 pytestmark = pytest.mark.gpu
 
@@ -24,6 +24,7 @@ def oracle_step(w, cfg, W, inputs, step, dtype=np.float64):
 def check(got_lat, got_eps, want_lat, want_eps, bf16):
     rl, re_ = rel_l2(got_lat, want_lat), rel_l2(got_eps, want_eps)
     ma = max_abs(got_lat, want_lat)
+    record(latent_rel_l2=rl, latent_max_abs=ma, eps_rel_l2=re_)
     if bf16:
         assert rl <= BF16_REL and ma <= BF16_ABS, (rl, ma, re_)
         assert re_ <= 2e-2, re_          # the noise estimate itself, not diluted by the latent
@@ -78,12 +79,14 @@ def test_cfg4_bf16_full3d_block_sampled_rows(fc):
     rows = np.concatenate([rows, [0, cfg.video_tokens - 1, 17549 - 45]])
     want = dit.forward(cfg, W, lat[0], cond[0], 500, dtype=np.float32, video_rows=rows)
     got = dit.patchify(got_eps[0], cfg.patch)[rows]
+    record(eps_rel_l2=rel_l2(got, want), eps_max_abs=max_abs(got, want))
     assert rel_l2(got, want) <= 2e-2, rel_l2(got, want)
     assert max_abs(got, want) <= BF16_ABS
     # latent update on those patches
     _, a_t, a_p = sampler.step_coefficients(w.schedule, w.step)
     want_lat = sampler.ddim_update(dit.patchify(lat[0].astype(np.float64), cfg.patch)[rows], want, a_t, a_p)
     got_l = dit.patchify(got_lat[0], cfg.patch)[rows]
+    record(latent_rel_l2=rel_l2(got_l, want_lat), latent_max_abs=max_abs(got_l, want_lat))
     assert rel_l2(got_l, want_lat) <= BF16_REL and max_abs(got_l, want_lat) <= BF16_ABS
 
 
@@ -162,6 +165,7 @@ def test_cfg5b_resume_trajectory_and_invariants(fc):
             torch.cuda.synchronize()
             finals[k] = host(d_lat)
             want = sampler.denoise_resume(cfg, W, lat, cond, null, w.schedule, k)
+            record(resume_from=float(k), final_latent_rel_l2=rel_l2(finals[k], want))
             assert rel_l2(finals[k], want) <= 1e-3, (k, rel_l2(finals[k], want))
         # a hit at k followed by single steps == one resume call, bit for bit
         d_lat = dev(lat)

@@ -1,5 +1,16 @@
 """Helpers shared by the GPU parity tests: device staging and error measures."""
+import os
+
 import numpy as np
+
+# measured errors of the parity tests, printed as a table at the end of the run
+PARITY = []
+
+
+def record(**values):
+    """Notes measured errors under the running test's name."""
+    test = os.environ.get("PYTEST_CURRENT_TEST", "?").split("::")[-1].split(" ")[0]
+    PARITY.append((test, values))
 
 
 def rel_l2(got, want):
