@@ -206,6 +206,157 @@ static hipError_t run_short_strided(const AttnParams& p, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- short strided sequences on the matrix cores
+// Same problem as above for bf16 and T <= 16: the scalar kernel spends its time in
+// bf16->fp32 unpacking and 2 T HD FMAs per query; here one wave does a sequence with
+// 3 + HD/16 small MFMAs and the kernel is bound by reading q, k, v and writing o once.
+//   S^T (16 keys x 16 queries) = K (A operand) x Q^T (B operand), v_mfma_f32_16x16x32_bf16,
+//   contraction over the head dim in steps of 32.  Operand lane l = (i, h), i = l % 16,
+//   h = l / 16: row/column i, k = 8h .. 8h+7.  D: column i, rows 4h + e in register e.
+//   So lane (i, h) holds the scores of query i against keys 4h .. 4h+3: after exp2 and
+//   rounding they are, as they stand, the B operand (k = 4h .. 4h+3) of
+//   O^T (16 dims x 16 queries) += V^T (A operand) x P^T, v_mfma_f32_16x16x16_bf16, whose
+//   A fragments (dim i, keys 4h .. 4h+3) are transpose reads of the row-major V tile.
+// A workgroup of 4 waves stages SM_SB neighbouring sequences ([SB][16][PITCH] per tensor,
+// coalesced: for one t the SB rows are contiguous in memory); each wave then takes
+// SM_SB / 4 of them.  PITCH/8 is odd so that the 16 rows of a fragment read fall into
+// distinct bank groups.
+typedef __attribute__((ext_vector_type(4))) short i16x4;
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
+constexpr int SM_SB = 8;
+template <int HD>
+struct ShortMfmaCfg {
+  static constexpr int PITCH = ((HD / 8) % 2 == 1) ? HD : HD + 8;      // elements
+  static constexpr int TILE = SM_SB * 16 * PITCH;                        // elements per tensor
+  static constexpr size_t SMEM = (size_t)3 * TILE * sizeof(bf16_t) + 64; // slack: the last V fragment reads past HD
+  static constexpr int KSTEPS = (HD + 31) / 32;
+  static constexpr int DT = (HD + 15) / 16;
+};
+
+template <int HD>
+__global__ __launch_bounds__(256) void k_attn_short_mfma(AttnParams p) {
+  using C = ShortMfmaCfg<HD>;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_sm[];
+  bf16_t* qs = (bf16_t*)smem_sm;
+  bf16_t* ks = qs + C::TILE;
+  bf16_t* vs = ks + C::TILE;
+  const int Tn = p.nq;                       // == nk, <= 16
+  const int sblocks = (p.groups + SM_SB - 1) / SM_SB;
+  int bid = blockIdx.x;
+  const int sb = bid % sblocks; bid /= sblocks;
+  const int head = bid % p.heads;
+  const int b = bid / p.heads;
+  const int s0 = sb * SM_SB;
+  const size_t bh = ((size_t)b * p.heads + head) * (size_t)p.q_tokens;
+  const bf16_t* qg = (const bf16_t*)p.q + bh * HD;
+  const bf16_t* kg = (const bf16_t*)p.k + bh * HD;
+  const bf16_t* vg = (const bf16_t*)p.v + bh * HD;
+
+  // ---- stage: rows t >= Tn are zero (V rows of masked keys must not hold NaN patterns)
+  constexpr int CPR = HD / 8;
+  for (int ch = threadIdx.x; ch < 16 * SM_SB * CPR; ch += 256) {
+    const int c = ch % CPR, r = ch / CPR;
+    const int sq = r % SM_SB, t = r / SM_SB;
+    const int loff = (sq * 16 + t) * C::PITCH + c * 8;
+    f32x4 zq = {0.0f, 0.0f, 0.0f, 0.0f}, zk = zq, zv = zq;
+    if (t < Tn) {
+      int sg = s0 + sq; sg = sg < p.groups ? sg : p.groups - 1;   // sequences past the last are never stored
+      const size_t goff = ((size_t)t * p.q_istride + sg) * HD + c * 8;
+      zq = *(const f32x4*)(qg + goff);
+      zk = *(const f32x4*)(kg + goff);
+      zv = *(const f32x4*)(vg + goff);
+    }
+    *(f32x4*)(qs + loff) = zq;
+    *(f32x4*)(ks + loff) = zk;
+    *(f32x4*)(vs + loff) = zv;
+  }
+  __syncthreads();
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int li = lane & 15, lh = lane >> 4;
+  const int tr_r = li >> 2, tr_a = li & 3;
+#pragma unroll
+  for (int w = 0; w < SM_SB / 4; ++w) {
+    const int sq = wave * (SM_SB / 4) + w;
+    if (s0 + sq >= p.groups) break;                      // wave-uniform
+    const bf16_t* qrow = qs + (sq * 16 + li) * C::PITCH;
+    const bf16_t* krow = ks + (sq * 16 + li) * C::PITCH;
+    f32x4 sacc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int st = 0; st < C::KSTEPS; ++st) {
+      const int d0 = 32 * st + 8 * lh;
+      bf16x8 qf, kf;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { qf[e] = (bf16_t)0.0f; kf[e] = (bf16_t)0.0f; }
+      if (d0 < HD) {                                     // HD % 8 == 0: a fragment is all in or all out
+        qf = *(const bf16x8*)(qrow + d0);
+        kf = *(const bf16x8*)(krow + d0);
+      }
+      sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf, sacc, 0, 0, 0);
+    }
+    // ---- softmax over the 16 keys of query li: 4 here, the rest in lanes li + 16 h'
+    float sc[4];
+    float mx = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      sc[e] = (4 * lh + e < Tn) ? sacc[e] * p.scale_log2 : -INFINITY;
+      mx = fmaxf(mx, sc[e]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));              // finite: key 0 is valid
+    bf16x4 pb;
+    float sum = 0.0f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      pb[e] = (bf16_t)__builtin_amdgcn_exp2f(sc[e] - mx);
+      sum += (float)pb[e];
+    }
+    sum += __shfl_xor(sum, 16, 64);
+    sum += __shfl_xor(sum, 32, 64);
+    const float inv = 1.0f / sum;
+    const i16x4 pf = __builtin_bit_cast(i16x4, pb);
+
+    const int tok = li * p.q_istride + s0 + sq;
+    bf16_t* orow = (bf16_t*)p.out + ((size_t)b * p.q_tokens + tok) * ((size_t)p.heads * HD) + (size_t)head * HD;
+    const bf16_t* vtile = vs + (sq * 16 + 4 * lh + tr_r) * C::PITCH + 4 * tr_a;
+#pragma unroll
+    for (int c = 0; c < C::DT; ++c) {
+      const bf16x4 vf = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(vtile + 16 * c));
+      f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+      const f32x4 o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(i16x4, vf), pf, zero, 0, 0, 0);
+      const int dd = 16 * c + 4 * lh;
+      if (li < Tn && dd < HD) {
+        bf16x4 ov;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)(o[e] * inv);
+        *(bf16x4*)(orow + dd) = ov;
+      }
+    }
+  }
+}
+
+static bool short_mfma_ok(const AttnParams& p) {
+  return (p.hd == 64 || p.hd == 72) && p.nq == p.nk && p.nq >= 1 && p.nq <= 16 && p.q_gstride == 1 &&
+         p.k_gstride == 1 && p.q_istride == p.k_istride && p.q_istride == p.groups && p.q_tokens == p.k_tokens &&
+         !p.kv_shared_tail;
+}
+
+template <int HD>
+static hipError_t run_short_mfma(const AttnParams& p, hipStream_t s) {
+  using C = ShortMfmaCfg<HD>;
+  const long long blocks = (long long)p.B * p.heads * ((p.groups + SM_SB - 1) / SM_SB);
+  if (blocks == 0) return hipSuccess;
+  auto kern = k_attn_short_mfma<HD>;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::SMEM);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  kern<<<(unsigned)blocks, 256, C::SMEM, s>>>(p);
+  return hipGetLastError();
+}
+
 template <typename T, int HD>
 static hipError_t run_non_mfma(const AttnParams& p, bool allow_short, hipStream_t s) {
   if (allow_short && short_strided_ok(p, sizeof(T))) return run_short_strided<T, HD>(p, s);
@@ -227,8 +378,8 @@ static hipError_t dispatch_plain(const AttnParams& p, bool allow_short, hipStrea
 }
 
 // ---------------------------------------------------------------- flash kernel (bf16, MFMA)
-// Workgroup = 4 waves; wave w owns query rows [64w, 64w+64) of a 256-row query tile
-// (two 32-column MFMA tiles qt).  Keys are walked in tiles of 64, staged in LDS as
+// Workgroup = 4 waves; wave w owns 32 QT query rows of a 128 QT-row query tile (QT = 1
+// or 2 32-column MFMA tiles qt).  Keys are walked in tiles of 64, staged in LDS as
 // K [64][HDP] and V [64][HDV] (double-buffered, register-prefetched).
 //
 // Per key tile and wave:
@@ -248,7 +399,6 @@ static hipError_t dispatch_plain(const AttnParams& p, bool allow_short, hipStrea
 //
 // HD = true head dim; HDP = HD rounded up to 16 (contraction of Q K^T); HDV = HD
 // rounded up to 32 (rows of O^T).  Pad lanes are zero-filled when staged.
-typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 template <int HD>
@@ -265,8 +415,9 @@ struct FlashCfg {
   static constexpr int CHUNKS = 64 * CH;     // per tile, K and V alike
 };
 
-template <int HD>
-__global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnParams p) {
+template <int HD, int QT>
+__global__ __launch_bounds__(256, ((HD <= 64 || QT == 1) ? 2 : 1)) void k_attn_flash(AttnParams p) {
+  constexpr int QROWS = 128 * QT;           // query rows per workgroup
   using C = FlashCfg<HD>;
   static_assert(HD % 8 == 0, "head dim must be a multiple of 8");
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -277,7 +428,7 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
   const int li = lane & 31, lh = lane >> 5;
 
   // problem and query tile of this workgroup
-  const int qtiles = (p.nq + 255) / 256;
+  const int qtiles = (p.nq + QROWS - 1) / QROWS;
   const long long work = xcd_work_item((long long)p.B * p.heads * p.groups * qtiles);
   if (work < 0) return;
   int bid = (int)work;
@@ -294,10 +445,10 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
                                               (size_t)g * p.k_gstride) * HD;
 
   // ---- Q fragments: B operand, lane (i, h) holds Q[row i][16s + 8h .. +7]
-  bf16x8 qf[2][C::KS];
-  const int q0 = qtile * 256 + wave * 64;
+  bf16x8 qf[QT][C::KS];
+  const int q0 = qtile * QROWS + wave * (32 * QT);
 #pragma unroll
-  for (int qt = 0; qt < 2; ++qt) {
+  for (int qt = 0; qt < QT; ++qt) {
     int qi = q0 + qt * 32 + li;
     qi = qi < p.nq ? qi : p.nq - 1;
     const bf16_t* qr = qbase + (size_t)(g * p.q_gstride + qi) * HD;
@@ -318,14 +469,14 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
     }
   }
 
-  f32x16 oacc[C::CT][2];
+  f32x16 oacc[C::CT][QT];
 #pragma unroll
   for (int c = 0; c < C::CT; ++c)
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt)
+    for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
       for (int r = 0; r < 16; ++r) oacc[c][qt][r] = 0.0f;
-  float lrow[2] = {0.0f, 0.0f};             // this lane's partial sum (its 32 of the 64 keys per tile)
+  float lrow[QT] = {};             // this lane's partial sum (its 32 of the 64 keys per tile)
 
   // ---- staging: K and V tiles are both [64 keys][HD] row-major, one 16-byte chunk per thread and pass
   constexpr int CPT = (C::CHUNKS + 255) / 256;
@@ -388,9 +539,9 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
 
   // minus the running reference of each query column, splat over an accumulator: it is the C
   // operand of the first score MFMA of every tile, so no per-tile accumulator initialisation
-  f32x16 negm[2];
+  f32x16 negm[QT];
 #pragma unroll
-  for (int qt = 0; qt < 2; ++qt)
+  for (int qt = 0; qt < QT; ++qt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) negm[qt][r] = 0.0f;
   bf16x2 ones;
@@ -406,7 +557,7 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
     const bf16_t* vs = Vs + buf * C::V_ELEMS;
 
     // ---- S^T = K Q^T - m (Q carries the factor scale*log2(e))
-    f32x16 sacc[2][2];
+    f32x16 sacc[2][QT];
 #pragma unroll
     for (int s = 0; s < C::KS; ++s) {
       bf16x8 kf[2];
@@ -415,7 +566,7 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int qt = 0; qt < 2; ++qt)
+        for (int qt = 0; qt < QT; ++qt)
           sacc[a][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[a], qf[qt][s], s == 0 ? negm[qt] : sacc[a][qt],
                                                                 0, 0, 0);
     }
@@ -430,7 +581,10 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
 #pragma unroll
           for (int e = 0; e < 4; ++e) {
             int key = 32 * a + 16 * (gg >> 1) + 8 * lh + 4 * (gg & 1) + e;
-            if (key >= rem) { sacc[a][0][4 * gg + e] = -INFINITY; sacc[a][1][4 * gg + e] = -INFINITY; }
+            if (key >= rem) {
+#pragma unroll
+              for (int qt = 0; qt < QT; ++qt) sacc[a][qt][4 * gg + e] = -INFINITY;
+            }
           }
     }
 
@@ -438,9 +592,9 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
     //      kLazy are let through (p <= 2^kLazy, harmless in fp32/bf16); only when a column
     //      exceeds it, or on the first tile, is m moved and O, l, S rescaled.  The branch is
     //      wave-uniform and rare after the first tiles.
-    float mx[2];
+    float mx[QT];
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < QT; ++qt) {
       float v = sacc[0][qt][0];
 #pragma unroll
       for (int a = 0; a < 2; ++a)
@@ -449,9 +603,12 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
       mx[qt] = fmaxf(v, __shfl_xor(v, 32, 64));     // finite: every tile has at least one valid key
     }
     const bool first = kt == 0;
-    if (__builtin_expect(__any(first || mx[0] > kLazy || mx[1] > kLazy), 0)) {
+    bool move = first;
 #pragma unroll
-      for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < QT; ++qt) move = move || mx[qt] > kLazy;
+    if (__builtin_expect(__any(move), 0)) {
+#pragma unroll
+      for (int qt = 0; qt < QT; ++qt) {
         const float delta = (first || mx[qt] > kLazy) ? mx[qt] : 0.0f;
         // on the first tile O and l are zero and exp2(-delta) may overflow: scale by 0 instead
         const float alpha = first ? 0.0f : __builtin_amdgcn_exp2f(-delta);
@@ -471,9 +628,9 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
 
     // ---- P = exp2(S), packed to bf16 in B-operand order; the row sum adds the rounded
     //      values (dot2 with ones), i.e. exactly what multiplies V.
-    bf16x8 pf[2][2][2];       // [qt][a][s2]
+    bf16x8 pf[QT][2][2];      // [qt][a][s2]
 #pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
+    for (int qt = 0; qt < QT; ++qt) {
       float sum = lrow[qt];
 #pragma unroll
       for (int a = 0; a < 2; ++a)
@@ -510,7 +667,7 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
 #pragma unroll
         for (int c = 0; c < C::CT; ++c)
 #pragma unroll
-          for (int qt = 0; qt < 2; ++qt)
+          for (int qt = 0; qt < QT; ++qt)
             oacc[c][qt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[c], pf[qt][a][s2], oacc[c][qt], 0, 0, 0);
       }
 
@@ -526,7 +683,7 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
   //      dims 32c + 8g + 4h + e in register 4g + e.
   bf16_t* obase = (bf16_t*)p.out + (size_t)b * p.q_tokens * ((size_t)p.heads * HD) + (size_t)head * HD;
 #pragma unroll
-  for (int qt = 0; qt < 2; ++qt) {
+  for (int qt = 0; qt < QT; ++qt) {
     const float ltot = lrow[qt] + __shfl_xor(lrow[qt], 32, 64);
     const float inv = 1.0f / ltot;
     const int qi = q0 + qt * 32 + li;
@@ -548,17 +705,17 @@ __global__ __launch_bounds__(256, (HD <= 64 ? 2 : 1)) void k_attn_flash(AttnPara
   }
 }
 
-template <int HD>
+template <int HD, int QT>
 static hipError_t run_flash(const AttnParams& p, hipStream_t s) {
   using C = FlashCfg<HD>;
-  auto kern = k_attn_flash<HD>;
+  auto kern = k_attn_flash<HD, QT>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::SMEM);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  long long blocks = (long long)p.B * p.heads * p.groups * ((p.nq + 255) / 256);
+  long long blocks = (long long)p.B * p.heads * p.groups * ((p.nq + 128 * QT - 1) / (128 * QT));
   if (blocks == 0) return hipSuccess;
   blocks = (blocks + 7) / 8 * 8;                     // whole rounds over the 8 XCDs
   kern<<<(unsigned)blocks, 256, C::SMEM, s>>>(p);
@@ -580,8 +737,16 @@ hipError_t launch_attention(int bf16, const AttnParams& p, int impl, hipStream_t
   if ((((uintptr_t)p.q | (uintptr_t)p.k | (uintptr_t)p.v | (uintptr_t)p.out) & 15) != 0) return hipErrorInvalidValue;
   if (!bf16) return dispatch_plain<float>(p, impl != 1, s);
   if (impl == 0 && flash_ok(p)) {
-    if (p.hd == 64) return run_flash<64>(p, s);
-    if (p.hd == 72) return run_flash<72>(p, s);
+    // One 32-query tile per wave (half the registers, twice the workgroups) when the key
+    // sequence is short: the work per workgroup is then a few tiles and the launch lives
+    // on how many workgroups a CU can hold, not on operand reuse.
+    const bool narrow = p.nk <= 512;
+    if (p.hd == 64) return narrow ? run_flash<64, 1>(p, s) : run_flash<64, 2>(p, s);
+    if (p.hd == 72) return narrow ? run_flash<72, 1>(p, s) : run_flash<72, 2>(p, s);
+  }
+  if (impl == 0 && short_mfma_ok(p)) {
+    if (p.hd == 64) return run_short_mfma<64>(p, s);
+    if (p.hd == 72) return run_short_mfma<72>(p, s);
   }
   return dispatch_plain<bf16_t>(p, impl != 1, s);
 }
