@@ -46,10 +46,14 @@ inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 inline size_t round_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
 
 // ---------------------------------------------------------------- GEMM epilogues
-// Every GEMM kernel hands its accumulators to an epilogue as groups of four
-// consecutive rows (m0..m0+3) of one column n, the natural unit of the 32x32 MFMA
-// accumulator layout.  `Mvalid` bounds rows, `Nvalid` bounds columns.  Column-only
-// quantities (bias, gate, head and patch decomposition) are hoisted into a `Col`.
+// Two interfaces, one arithmetic.
+//  * Column form (plain kernel, and the MFMA kernel for EPI_UNPATCH): four consecutive
+//    rows (m0..m0+3) of one column n; column-only quantities are hoisted into a `Col`.
+//  * Row-run form (MFMA kernel, every mode whose output rows are contiguous along n):
+//    `apply4` turns four consecutive columns of one row into final values (bias,
+//    activation, gate or q scale), `run8` gives the address of eight consecutive outputs
+//    of a row, which the kernel writes with one 16-byte store.
+// `Mvalid` bounds rows, `Nvalid` bounds columns.
 
 enum EpiMode : int {
   EPI_STORE = 0,     // out[m,n] = acc + bias
@@ -92,11 +96,17 @@ struct Epilogue {
   int Mvalid, Nvalid;
   FastDiv rows_per_b;          // EPI_HEADS: tokens;  EPI_UNPATCH: T*S
   FastDiv unp_S, unp_gw;       // EPI_UNPATCH
+  FastDiv col_D, col_hd;       // EPI_HEADS, row-run form
+  static constexpr bool kRowRuns = MODE != EPI_UNPATCH;
 
   // host side: fills the divisors the mode needs
   static Epilogue make(const EpiParams& p, int M, int N) {
-    Epilogue e{p, M, N, FastDiv(), FastDiv(), FastDiv()};
-    if (MODE == EPI_HEADS) e.rows_per_b = FastDiv((unsigned)p.tokens);
+    Epilogue e{p, M, N, FastDiv(), FastDiv(), FastDiv(), FastDiv(), FastDiv()};
+    if (MODE == EPI_HEADS) {
+      e.rows_per_b = FastDiv((unsigned)p.tokens);
+      e.col_D = FastDiv((unsigned)p.D);
+      e.col_hd = FastDiv((unsigned)p.hd);
+    }
     if (MODE == EPI_UNPATCH) {
       const int gw = p.W / p.p, S = gw * (p.H / p.p);
       e.rows_per_b = FastDiv((unsigned)(p.T * S));
@@ -136,6 +146,46 @@ struct Epilogue {
       c.foff = ((size_t)dh * P.W + dw) * P.C + ch;
     }
     return c;
+  }
+
+  // Row-run form.  Preconditions (checked by the dispatcher): Nvalid, ldo, hd and D are
+  // multiples of 8; bias, gate and the output tensors are 16-byte aligned.
+  // v: accumulators of columns n0..n0+3 (n0 % 4 == 0) of one row -> final values.
+  __device__ __forceinline__ void apply4(int n0, float (&v)[4]) const {
+    if (n0 >= Nvalid) return;                 // never stored
+    if (P.bias) {
+      const f32x4 b = *(const f32x4*)(P.bias + n0);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] += b[e];
+    }
+    if constexpr (MODE == EPI_GELU) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = gelu_tanh_f(v[e]);
+    } else if constexpr (MODE == EPI_GATE) {
+      if (P.gate) {
+        const f32x4 g = *(const f32x4*)(P.gate + n0);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] *= g[e];
+      }
+    } else if constexpr (MODE == EPI_HEADS) {
+      if (P.which0 + (int)col_D.div((unsigned)n0) == 0) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] *= P.qscale;
+      }
+    }
+  }
+  // Address of outputs (m, n0 .. n0+7), n0 % 8 == 0: one 16-byte run in every row-run mode.
+  __device__ __forceinline__ T* run8(int m, int n0) const {
+    if constexpr (MODE == EPI_HEADS) {
+      const unsigned w = col_D.div((unsigned)n0), cc = (unsigned)n0 - w * col_D.d;
+      const unsigned head = col_hd.div(cc), dd = cc - head * col_hd.d;
+      const int which = P.which0 + (int)w;
+      const unsigned bb = rows_per_b.div((unsigned)m);
+      T* base = (T*)(which == 0 ? P.q : which == 1 ? P.k : P.v);
+      return base + ((size_t)head * P.tokens + (size_t)m + (size_t)bb * (P.heads - 1) * P.tokens) * P.hd + dd;
+    } else {
+      return (T*)P.out + (size_t)m * P.ldo + n0;
+    }
   }
 
   // Four consecutive rows m0..m0+3 of column c (the unit of the 32x32 MFMA accumulator).

@@ -151,7 +151,11 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
       for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+          // row-run epilogues want a lane to hold consecutive n: D rows come from the A
+          // operand, so the weight fragment goes there (the operand layouts are alike)
+          acc[i][j] = Epi::kRowRuns
+                          ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks & 1][j], fa[ks & 1][i], acc[i][j], 0, 0, 0)
+                          : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
     }
     constexpr int kDsRead = 0x100, kMfma = 0x008;
     __builtin_amdgcn_sched_group_barrier(kDsRead, TM + TN, 0);
@@ -167,18 +171,55 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
     __builtin_amdgcn_sched_group_barrier(kMfma, TM * TN, 0);
   }
 
+  if constexpr (Epi::kRowRuns) {
+    // Accumulator lane (li, lh) holds row m = 32 i + li, columns 32 j + 8 g + 4 lh + e.
+    // The finished bf16 values go through this wave's slice of the (now idle) operand
+    // stages, XOR-swizzled by 16-byte chunk, and leave as 16-byte stores: a wave-store
+    // covers whole 2 WTN-byte row segments instead of 2 bytes per lane.
+    __syncthreads();                                  // every wave is done reading the stages
+    constexpr int ROWB = WTN * 2;                     // bytes per staged row
+    constexpr int CPRW = WTN / 8;                     // 16-byte chunks per row
+    constexpr int RPLC = 256 / ROWB > 0 ? 256 / ROWB : 1;   // rows per 256-byte LDS line
+    static_assert(NW * WTM * ROWB <= S * STAGE_BYTES, "staging area");
+    unsigned char* cst = smem + wave * (WTM * ROWB);
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const auto col = epi.col(bn0 + wc * WTN + j * 32 + li);
+    for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int m0 = bm0 + wr * WTM + i * 32 + g * 8 + lh * 4;
-        float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-        epi.store4(col, m0, v);
+        const int n0 = bn0 + wc * WTN + j * 32 + g * 8 + lh * 4;
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+          float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          epi.apply4(n0, v);
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (bf16_t)v[e];
+          const int row = i * 32 + li, chunk = 4 * j + g;
+          *(bf16x4*)(cst + row * ROWB + ((chunk ^ ((row / RPLC) & (CPRW - 1))) << 4) + lh * 8) = o;
+        }
       }
+    constexpr int RPI = 64 / CPRW;                    // rows per wave-store
+#pragma unroll
+    for (int it = 0; it < WTM / RPI; ++it) {
+      const int row = it * RPI + lane / CPRW, chunk = lane % CPRW;
+      const bf16x8 o = *(const bf16x8*)(cst + row * ROWB + ((chunk ^ ((row / RPLC) & (CPRW - 1))) << 4));
+      const int m = bm0 + wr * WTM + row, n0 = bn0 + wc * WTN + chunk * 8;
+      if (m < M && n0 < N) __builtin_nontemporal_store(o, (bf16x8*)epi.run8(m, n0));
     }
+  } else {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const auto col = epi.col(bn0 + wc * WTN + j * 32 + li);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int m0 = bm0 + wr * WTM + i * 32 + g * 8 + lh * 4;
+          float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          epi.store4(col, m0, v);
+        }
+      }
+  }
 }
 
 // ---------------------------------------------------------------- plain kernel (any T, any shape)
@@ -254,7 +295,16 @@ template <int MODE>
 static hipError_t dispatch_mode(int bf16, const void* A, const void* Wt, int M, int N, int K, const EpiParams& ep,
                                 hipStream_t s) {
   if (!bf16) return run_plain<float, MODE>(A, Wt, M, N, K, ep, s);
-  const bool aligned = (((uintptr_t)A | (uintptr_t)Wt) & 15) == 0;
+  bool aligned = (((uintptr_t)A | (uintptr_t)Wt) & 15) == 0;
+  if (MODE != EPI_UNPATCH) {
+    // the MFMA kernel writes 16-byte runs of a row and reads bias / gate four at a time
+    aligned = aligned && N % 8 == 0 && (((uintptr_t)ep.bias | (uintptr_t)ep.gate) & 15) == 0;
+    if (MODE == EPI_HEADS)
+      aligned = aligned && ep.hd % 8 == 0 && ep.D % 8 == 0 &&
+                (((uintptr_t)ep.q | (uintptr_t)ep.k | (uintptr_t)ep.v) & 15) == 0;
+    else
+      aligned = aligned && ep.ldo % 8 == 0 && ((uintptr_t)ep.out & 15) == 0;
+  }
   if (K % 64 != 0 || !aligned || N < 32) return run_plain<bf16_t, MODE>(A, Wt, M, N, K, ep, s);
   // Tile choice.  256x256 (8 waves, one workgroup per CU) has the best operand reuse but
   // needs several rounds of tiles per CU and wastes the ragged part of N; 128x128 (4
