@@ -156,8 +156,11 @@ const char* fc_last_error(void);
  * recorded events, adds the elapsed milliseconds and the number of brackets per
  * category into ms_out / launches_out (host arrays of n >= fc_profile_categories()
  * entries) and clears the record.  Categories are named by
- * fc_profile_category_name(i).  fc_profile_categories() returns the count, not a status. */
+ * fc_profile_category_name(i).  fc_profile_categories() returns the count, not a status.
+ * fc_profile_select() restricts the brackets to one category (-1: all, the default), so
+ * that a timed run carries the events of the kernel of interest only. */
 int fc_profile_enable(fc_model* m, int32_t enable);
+int fc_profile_select(fc_model* m, int32_t category);
 int fc_profile_categories(void);
 const char* fc_profile_category_name(int32_t i);
 int fc_profile_read(fc_model* m, int32_t n, double* ms_out, int64_t* launches_out);

@@ -53,6 +53,7 @@ EXPORTS = {
                           C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p],
     "fc_schedule_coefficients": [C.POINTER(fc_schedule), C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_int32)],
     "fc_profile_enable": [C.c_void_p, C.c_int32],
+    "fc_profile_select": [C.c_void_p, C.c_int32],
     "fc_profile_categories": [],
     "fc_profile_read": [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)],
     "fc_op_linear": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
@@ -172,6 +173,16 @@ def fc_schedule_coefficients(sched: synth.Schedule, step: int):
 
 def fc_profile_enable(model: int, enable: bool) -> None:
     _check(_lib.fc_profile_enable(model, int(enable)), "fc_profile_enable")
+
+
+def fc_profile_select(model: int, category) -> None:
+    """Restrict the event brackets to one category (name or index); None or -1 = all."""
+    if category is None:
+        category = -1
+    if isinstance(category, str):
+        names = [fc_profile_category_name(i) for i in range(fc_profile_categories())]
+        category = names.index(category)
+    _check(_lib.fc_profile_select(model, int(category)), "fc_profile_select")
 
 
 def fc_profile_categories() -> int:

@@ -44,6 +44,7 @@ const char* const kProfNames[PC_COUNT] = {
 
 struct Profiler {
   bool on = false;
+  int only = -1;            // -1: every category, else just this one
   struct Rec { hipEvent_t a, b; int cat; };
   std::vector<Rec> recs;
   std::vector<hipEvent_t> pool;
@@ -272,7 +273,7 @@ struct ProfScope {        // records an event pair around the launches made in i
   hipEvent_t a = nullptr, b = nullptr;
   int cat;
   ProfScope(const Ctx& c, int cat_) : s(c.s), cat(cat_) {
-    if (!c.m->prof.on) return;
+    if (!c.m->prof.on || (c.m->prof.only >= 0 && c.m->prof.only != cat_)) return;
     p = &c.m->prof;
     a = p->get(); b = p->get();
     if (!a || !b) { p = nullptr; return; }
@@ -694,6 +695,13 @@ int fc_profile_enable(fc_model* m, int32_t enable) {
   if (!m) return fail(FC_ERR_NULL, "NULL argument");
   m->prof.release_all();
   m->prof.on = enable != 0;
+  return FC_OK;
+}
+
+int fc_profile_select(fc_model* m, int32_t category) {
+  if (!m) return fail(FC_ERR_NULL, "NULL argument");
+  if (category < -1 || category >= PC_COUNT) return fail(FC_ERR_RANGE, "no such profile category");
+  m->prof.only = category;
   return FC_OK;
 }
 
