@@ -189,6 +189,16 @@ int fc_op_layernorm_modulate(int32_t dtype, float* x, const void* y, const float
                              const float* scale, void* out, int32_t M, int32_t D, float eps,
                              void* hip_stream);
 
+/* Patch embedding with positions: x[b, row_off + n, :] (f32, rows of D, rows_per_b rows per
+ * batch row) = patch(latent[b % R], n) . Wp[p*p*C, D] + bp[D] + pos_sp[s, :] + pos_t[t, :],
+ * n = t*S + s, S = (H/p)*(W/p), latent [R, T, H, W, C] f32, patch features in (dh, dw, c)
+ * order; all tensors f32.  impl 0: library's choice; 1: the general kernel; 2: the
+ * matrix-core kernel (p = 2, C = 16, D a multiple of 256; FC_ERR_UNSUPPORTED otherwise). */
+int fc_op_patch_embed(const float* latent, int32_t R, int32_t B, const float* Wp, const float* bp,
+                      const float* pos_sp, const float* pos_t, float* x, int32_t T, int32_t H,
+                      int32_t W, int32_t C, int32_t p, int32_t D, int32_t rows_per_b,
+                      int32_t row_off, int32_t impl, void* hip_stream);
+
 /* Fused guidance + DDIM update on n elements per request, R requests:
  * eps = eps_u + s (eps_c - eps_u) (eps_u NULL: eps = eps_c);
  * x <- c[2] * (x - c[1] eps) / c[0] + c[3] eps, c = fc_schedule_coefficients.

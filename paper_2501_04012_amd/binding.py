@@ -62,6 +62,9 @@ EXPORTS = {
                         C.c_int32, C.c_int32, C.c_void_p],
     "fc_op_layernorm_modulate": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                  C.c_int32, C.c_float, C.c_void_p],
+    "fc_op_patch_embed": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                          C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                          C.c_int32, C.c_void_p],
     "fc_op_cfg_ddim": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_float,
                        C.POINTER(C.c_float), C.c_void_p],
 }
@@ -215,6 +218,12 @@ def fc_op_attention(dtype, q, k, v, out, G, nq, nk, d, impl=0, stream=None) -> N
 def fc_op_layernorm_modulate(dtype, x, y, shift, scale, out, M, D, eps, stream=None) -> None:
     _check(_lib.fc_op_layernorm_modulate(dtype, _ptr(x), _ptr(y), _ptr(shift), _ptr(scale), _ptr(out), M, D, eps,
                                          _stream(stream)), "fc_op_layernorm_modulate")
+
+
+def fc_op_patch_embed(latent, R, B, Wp, bp, pos_sp, pos_t, x, T, H, W, Cc, p, D, rows_per_b, row_off, impl=0,
+                      stream=None) -> None:
+    _check(_lib.fc_op_patch_embed(_ptr(latent), R, B, _ptr(Wp), _ptr(bp), _ptr(pos_sp), _ptr(pos_t), _ptr(x), T, H, W,
+                                  Cc, p, D, rows_per_b, row_off, impl, _stream(stream)), "fc_op_patch_embed")
 
 
 def fc_op_cfg_ddim(x, eps_c, eps_u, eps_out, n_total, guidance_scale, coef4, stream=None) -> None:

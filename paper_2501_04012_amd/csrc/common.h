@@ -34,12 +34,14 @@ __device__ __forceinline__ float wave_max(float v) {
 
 __device__ __forceinline__ float silu_f(float v) { return v / (1.0f + __expf(-v)); }
 
-// GELU, tanh form.  tanh(u) = 1 - 2/(exp(2u)+1) stays finite for large |u|.
+// GELU, tanh form: 0.5 v (1 + tanh(u)) = v / (1 + exp(-2u)), u = c (v + 0.044715 v^3).
+// One exp2 and one reciprocal (hardware approximations, about 1 ulp; the callers round
+// to bf16 or compare at 1e-4); finite at both ends: exp2 -> inf gives v * 0.
 __device__ __forceinline__ float gelu_tanh_f(float v) {
-  const float c = 0.7978845608028654f;
-  float u = c * (v + 0.044715f * v * v * v);
-  float t = 1.0f - 2.0f / (__expf(2.0f * u) + 1.0f);
-  return 0.5f * v * (1.0f + t);
+  const float k1 = -2.0f * 0.7978845608028654f * 1.4426950408889634f;   // -2 c log2(e)
+  const float k2 = k1 * 0.044715f;
+  const float e = __builtin_amdgcn_exp2f(v * __builtin_fmaf(v * v, k2, k1));
+  return v * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
 inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
@@ -245,7 +247,7 @@ hipError_t launch_gemv(int bf16, const float* in, int K, const void* Wt, const f
                        size_t out_layer_stride, hipStream_t s);
 hipError_t launch_patch_embed(const float* latent, int R, int B, const float* Wp, const float* bp,
                               const float* pos_sp, const float* pos_t, float* x, int T, int H, int W, int C,
-                              int p, int D, int rows_per_b, int row_off, hipStream_t s);
+                              int p, int D, int rows_per_b, int row_off, int impl, hipStream_t s);
 hipError_t launch_ln_modulate(int bf16, float* x, const void* y, const float* shift, const float* scale, void* out,
                               int rows, int D, float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off,
                               hipStream_t s);

@@ -197,10 +197,133 @@ __global__ void k_patch_embed(const float* __restrict__ latent, int R, const flo
   }
 }
 
+// K = 64 as 2x2 patches of 16 channels: enough arithmetic (2 N D 64 FLOP) to keep the
+// vector ALU busy for several times longer than the write of x takes, so this shape goes
+// to the matrix cores.  Both fp32 operands are split into bf16 high and low parts and
+// the product is taken as hi*hi + hi*lo + lo*hi (v_mfma_f32_32x32x16_bf16, fp32
+// accumulation): the dropped lo*lo term is below 2^-16 of a product.
+//   A operand: lane (i, h) = token i of a 32-position tile.  Patch feature order is
+//   (dh, dw, c), so features 32 dh .. 32 dh + 31 of a token are one contiguous run of the
+//   latent (row 2 hp + dh, pixels 2 wp and 2 wp + 1, 16 channels).  The contraction
+//   order is free as long as both operands agree: lane half h takes the run dh = h, and
+//   step s of 4 uses its elements 8 s .. 8 s + 7 (feature 32 h + 8 s + x); Wp rows are
+//   fetched in the same order.
+//   D: lane (i, h) holds column i of a 32-column tile, tokens 8 g + 4 h + e.
+// A block owns 32 spatial positions and 256 columns (4 waves x 2 column tiles) and walks
+// a run of (batch row, frame) pairs with its split weight fragments and bias + pos_sp in
+// registers (the latter as the C operand of the first MFMA); pos_t is added at the store.
+// The runs are cut so that the grid is several rounds of workgroups: a grid of slightly
+// more than one round would cost two.
+__device__ __forceinline__ void split_bf16(float v, bf16_t& hi, bf16_t& lo) {
+  hi = (bf16_t)v;
+  lo = (bf16_t)(v - (float)hi);
+}
+
+__global__ __launch_bounds__(256) void k_patch_embed_mfma(const float* __restrict__ latent, int R, int B,
+                                                          const float* __restrict__ Wp, const float* __restrict__ bp,
+                                                          const float* __restrict__ pos_sp,
+                                                          const float* __restrict__ pos_t, float* __restrict__ x, int T,
+                                                          int H, int W, int D, int rows_per_b, int row_off, int frames_per_block) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, li = lane & 31, lh = lane >> 5;
+  const int gw = W / 2, S = (H / 2) * gw;
+  const int s0 = blockIdx.x * 32;
+  const int col0 = blockIdx.y * 256 + wave * 64;
+  const int bt0 = blockIdx.z * frames_per_block;
+  const int bt1 = min(bt0 + frames_per_block, B * T);
+  const int s_l = s0 + li < S ? s0 + li : S - 1;          // rows past S are computed from a valid token, never stored
+  const size_t a_off = ((size_t)((s_l / gw) * 2 + lh) * W + (size_t)(s_l % gw) * 2) * 16;
+  f32x16 base[2];
+  bf16x8 w_hi[2][4], w_lo[2][4];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int col = col0 + 32 * j + li;
+    const float bias = bp[col];
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int tok = s0 + 8 * g + 4 * lh + e;
+        base[j][4 * g + e] = bias + pos_sp[(size_t)(tok < S ? tok : S - 1) * D + col];
+      }
+#pragma unroll
+    for (int st = 0; st < 4; ++st)
+#pragma unroll
+      for (int xx = 0; xx < 8; ++xx) {
+        bf16_t hi, lo;
+        split_bf16(Wp[(size_t)(32 * lh + 8 * st + xx) * D + col], hi, lo);
+        w_hi[j][st][xx] = hi;
+        w_lo[j][st][xx] = lo;
+      }
+  }
+  // the patch values of frame bt+1 are fetched while frame bt is multiplied and stored
+  const size_t frame = (size_t)H * W * 16;
+  f32x4 av[8], an[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q)
+    an[q] = *(const f32x4*)(latent + ((size_t)((bt0 / T) % R) * T + bt0 % T) * frame + a_off + 4 * q);
+  for (int bt = bt0; bt < bt1; ++bt) {
+    const int b = bt / T, t = bt % T;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) av[q] = an[q];
+    if (bt + 1 < bt1) {
+      const int b1 = (bt + 1) / T, t1 = (bt + 1) % T;
+      const float* ap = latent + ((size_t)(b1 % R) * T + t1) * frame + a_off;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) an[q] = *(const f32x4*)(ap + 4 * q);
+    }
+    f32x16 acc[2] = {base[0], base[1]};
+#pragma unroll
+    for (int st = 0; st < 4; ++st) {
+      bf16x8 a_hi, a_lo;
+#pragma unroll
+      for (int xx = 0; xx < 8; ++xx) {
+        bf16_t hi, lo;
+        split_bf16(av[2 * st + (xx >> 2)][xx & 3], hi, lo);
+        a_hi[xx] = hi;
+        a_lo[xx] = lo;
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, w_hi[j][st], acc[j], 0, 0, 0);
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_hi, w_lo[j][st], acc[j], 0, 0, 0);
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, w_hi[j][st], acc[j], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int col = col0 + 32 * j + li;
+      const float pt = pos_t[(size_t)t * D + col];
+      float* xc = x + ((size_t)b * rows_per_b + row_off + (size_t)t * S) * D + col;
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int tok = s0 + 8 * g + 4 * lh + e;
+          if (tok < S) xc[(size_t)tok * D] = acc[j][4 * g + e] + pt;
+        }
+    }
+  }
+}
+
+// impl 0: by shape; 1: general kernel; 2: matrix-core kernel (hipErrorInvalidValue if the shape does not fit it)
 hipError_t launch_patch_embed(const float* latent, int R, int B, const float* Wp, const float* bp,
                               const float* pos_sp, const float* pos_t, float* x, int T, int H, int W, int C,
-                              int p, int D, int rows_per_b, int row_off, hipStream_t s) {
-  int N = T * (H / p) * (W / p);
+                              int p, int D, int rows_per_b, int row_off, int impl, hipStream_t s) {
+  const int S = (H / p) * (W / p), N = T * S;
+  if (N == 0 || B == 0) return hipSuccess;
+  const bool mfma_fits = p == 2 && C == 16 && D % 256 == 0;
+  if (impl == 2 && !mfma_fits) return hipErrorInvalidValue;
+  // by shape: worth it once its grid fills the chip (every block walks all B*T frames)
+  if (impl == 2 || (impl == 0 && mfma_fits && (long long)ceil_div(S, 32) * (D / 256) >= 256)) {
+    const int tiles = ceil_div(S, 32) * (D / 256);
+    int runs = ceil_div(2048, tiles);
+    runs = runs < 1 ? 1 : (runs > B * T ? B * T : runs);
+    const int fpb = ceil_div(B * T, runs);
+    dim3 grid(ceil_div(S, 32), D / 256, ceil_div(B * T, fpb));
+    k_patch_embed_mfma<<<grid, 256, 0, s>>>(latent, R, B, Wp, bp, pos_sp, pos_t, x, T, H, W, D, rows_per_b, row_off,
+                                            fpb);
+    return hipGetLastError();
+  }
   dim3 grid(ceil_div(N, PE_TOK), B);
   size_t sh = (size_t)PE_TOK * p * p * C * sizeof(float);
   k_patch_embed<<<grid, 256, sh, s>>>(latent, R, Wp, bp, pos_sp, pos_t, x, T, H, W, C, p, D, rows_per_b, row_off);

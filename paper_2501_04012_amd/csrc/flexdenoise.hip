@@ -440,7 +440,7 @@ int run_step(const Ctx& c, float* latent, const fc_schedule* sched, int step, fl
   {
   ProfScope ps(c, PC_PATCH_EMBED);
   HIP_TRY(launch_patch_embed(latent, c.R, w.B, m->p_w, m->p_b, m->pos_sp, m->pos_t, w.x, cf.frames, cf.height,
-                             cf.width, cf.channels, cf.patch, D, m->Ns, text_rows, c.s));
+                             cf.width, cf.channels, cf.patch, D, m->Ns, text_rows, 0, c.s));
   if (text_rows)
     HIP_TRY(launch_act_to_f32_rows(m->bf16, w.y, w.x, w.B * cf.text_len, D, cf.text_len, m->Ns, 0, c.R, c.use_cfg,
                                    c.s));
@@ -759,6 +759,20 @@ int fc_op_layernorm_modulate(int32_t dtype, float* x, const void* y, const float
   if ((shift == nullptr) != (scale == nullptr)) return fail(FC_ERR_NULL, "shift and scale go together");
   if (M < 0 || D < 4 || D % 4 || D > 4096) return fail(FC_ERR_RANGE, "D must be a multiple of 4 in 4..4096");
   HIP_TRY(launch_ln_modulate(dtype == FC_BF16, x, y, shift, scale, out, M, D, eps, M > 0 ? M : 1, M > 0 ? M : 1, 0,
+                             (hipStream_t)stream));
+  return FC_OK;
+}
+
+int fc_op_patch_embed(const float* latent, int32_t R, int32_t B, const float* Wp, const float* bp, const float* pos_sp,
+                      const float* pos_t, float* x, int32_t T, int32_t H, int32_t W, int32_t C, int32_t p, int32_t D,
+                      int32_t rows_per_b, int32_t row_off, int32_t impl, void* stream) {
+  if (!latent || !Wp || !bp || !pos_sp || !pos_t || !x) return fail(FC_ERR_NULL, "NULL argument");
+  if (R < 1 || B < 0 || T < 1 || H < 1 || W < 1 || C < 1 || p < 1 || H % p || W % p || D < 4 || D % 4 || row_off < 0 ||
+      rows_per_b < row_off + T * (H / p) * (W / p) || impl < 0 || impl > 2)
+    return fail(FC_ERR_RANGE, "bad patch embedding shape");
+  if (impl == 2 && !(p == 2 && C == 16 && D % 256 == 0))
+    return fail(FC_ERR_UNSUPPORTED, "the matrix-core patch embedding needs p = 2, C = 16, D % 256 = 0");
+  HIP_TRY(launch_patch_embed(latent, R, B, Wp, bp, pos_sp, pos_t, x, T, H, W, C, p, D, rows_per_b, row_off, impl,
                              (hipStream_t)stream));
   return FC_OK;
 }

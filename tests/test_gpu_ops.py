@@ -165,6 +165,42 @@ def test_layernorm_modulate(fc, M, D, bf, mod):
     assert np.array_equal(host(dx), x)                        # no pending branch: x untouched
 
 
+@pytest.mark.parametrize("impl", [1, 2])
+@pytest.mark.parametrize("shape", [
+    # T, H, W, C, D, R, B, row_off
+    (3, 12, 20, 16, 256, 2, 4, 5),        # ragged spatial tile (60 positions), guidance rows reuse latents, text rows ahead
+    (2, 16, 16, 16, 512, 1, 1, 0),
+])
+def test_patch_embed_kernels(fc, shape, impl):
+    """Both patch-embedding kernels against patchify + matmul + position add in float64.
+    The matrix-core kernel multiplies bf16 high/low splits of both fp32 operands
+    (hi*hi + hi*lo + lo*hi): the bound is relative 2^-15 of sum |patch| |w| per output."""
+    import torch
+    T, H, W, C, D, R, B, row_off = shape
+    p = 2
+    rng = np.random.default_rng(1234)
+    S = (H // p) * (W // p)
+    lat = rng.standard_normal((R, T, H, W, C)).astype(np.float32)
+    Wp = (rng.standard_normal((p * p * C, D)) * 0.05).astype(np.float32)
+    bp = rng.standard_normal(D).astype(np.float32)
+    pos_sp = rng.standard_normal((S, D)).astype(np.float32)
+    pos_t = rng.standard_normal((T, D)).astype(np.float32)
+    rows_per_b = row_off + T * S + 3
+    x = torch.full((B, rows_per_b, D), -7.0, device="cuda:0")
+    fc.fc_op_patch_embed(dev(lat), R, B, dev(Wp), dev(bp), dev(pos_sp), dev(pos_t), x, T, H, W, C, p, D, rows_per_b,
+                         row_off, impl)
+    torch.cuda.synchronize()
+    got = host(x)
+    for b in range(B):
+        patches = dit.patchify(lat[b % R].astype(np.float64), p)
+        want = patches @ Wp.astype(np.float64) + bp + (pos_t[:, None, :] + pos_sp[None, :, :]).reshape(T * S, D)
+        bound = 2.0 ** -15 * (np.abs(patches) @ np.abs(Wp).astype(np.float64)) + 1e-5
+        assert (np.abs(got[b, row_off:row_off + T * S] - want) <= bound).all()
+        # rows outside the video tokens are not touched
+        assert (got[b, :row_off] == -7.0).all() and (got[b, row_off + T * S:] == -7.0).all()
+
+
+
 # --------------------------------------------------------------------------- guidance + DDIM
 
 @pytest.mark.parametrize("n", [1, 7, 4096, 65536 + 3])

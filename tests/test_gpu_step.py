@@ -57,6 +57,20 @@ def test_small_ragged_model_with_sharp_softmax(fc, mode, dtype):
     check(*got, *want, bf16=dtype == synth.DT_BF16)
 
 
+@pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
+def test_small_model_with_16_latent_channels(fc, dtype):
+    """2x2 patches of 16 channels (patch features K = 64, the shape of the full-3D
+    configuration's patch embedding), ragged spatial size, guidance, two requests."""
+    cfg = synth.ModelConfig(frames=3, height=12, width=20, channels=16, patch=2, hidden=256, heads=4, mlp_dim=512,
+                            depth=1, text_len=26, text_dim=96, attn_mode=synth.ATTN_FULL3D_CONCAT, dtype=dtype)
+    w = synth.Workload("small16", cfg, weight_seed=17, latent_seed=18, text_seed=19, null_seed=20, requests=2)
+    W = synth.make_weights(cfg, 17, std=0.05)
+    inputs = synth.workload_inputs(w)
+    got = run_step_gpu(fc, w, weights=W, inputs=inputs)
+    want = oracle_step(w, cfg, W, inputs, w.step)
+    check(*got, *want, bf16=dtype == synth.DT_BF16)
+
+
 def test_cfg2_bf16_factorized_block(fc):
     w = synth.WORKLOADS["cfg2"]
     W = synth.make_weights(w.model, w.weight_seed)
