@@ -180,7 +180,13 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
     constexpr int ROWB = WTN * 2;                     // bytes per staged row
     constexpr int CPRW = WTN / 8;                     // 16-byte chunks per row
     constexpr int RPLC = 256 / ROWB > 0 ? 256 / ROWB : 1;   // rows per 256-byte LDS line
+    constexpr bool POW2 = (CPRW & (CPRW - 1)) == 0;
     static_assert(NW * WTM * ROWB <= S * STAGE_BYTES, "staging area");
+    static_assert((WTM * CPRW) % 64 == 0, "whole wave-stores");
+    // chunk position inside a row: XOR with the line index (power-of-two rows), else a rotation
+    auto swz = [](int row, int chunk) {
+      return POW2 ? (chunk ^ ((row / RPLC) & (CPRW - 1))) : (chunk + row) % CPRW;
+    };
     unsigned char* cst = smem + wave * (WTM * ROWB);
 #pragma unroll
     for (int j = 0; j < TN; ++j)
@@ -195,14 +201,14 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
 #pragma unroll
           for (int e = 0; e < 4; ++e) o[e] = (bf16_t)v[e];
           const int row = i * 32 + li, chunk = 4 * j + g;
-          *(bf16x4*)(cst + row * ROWB + ((chunk ^ ((row / RPLC) & (CPRW - 1))) << 4) + lh * 8) = o;
+          *(bf16x4*)(cst + row * ROWB + (swz(row, chunk) << 4) + lh * 8) = o;
         }
       }
-    constexpr int RPI = 64 / CPRW;                    // rows per wave-store
 #pragma unroll
-    for (int it = 0; it < WTM / RPI; ++it) {
-      const int row = it * RPI + lane / CPRW, chunk = lane % CPRW;
-      const bf16x8 o = *(const bf16x8*)(cst + row * ROWB + ((chunk ^ ((row / RPLC) & (CPRW - 1))) << 4));
+    for (int it = 0; it < WTM * CPRW / 64; ++it) {
+      const int idx = it * 64 + lane;
+      const int row = idx / CPRW, chunk = idx % CPRW;
+      const bf16x8 o = *(const bf16x8*)(cst + row * ROWB + (swz(row, chunk) << 4));
       const int m = bm0 + wr * WTM + row, n0 = bn0 + wc * WTN + chunk * 8;
       if (m < M && n0 < N) __builtin_nontemporal_store(o, (bf16x8*)epi.run8(m, n0));
     }
@@ -307,11 +313,15 @@ static hipError_t dispatch_mode(int bf16, const void* A, const void* Wt, int M, 
   }
   if (K % 64 != 0 || !aligned || N < 32) return run_plain<bf16_t, MODE>(A, Wt, M, N, K, ep, s);
   // Tile choice.  256x256 (8 waves, one workgroup per CU) has the best operand reuse but
-  // needs several rounds of tiles per CU and wastes the ragged part of N; 128x128 (4
-  // waves, two workgroups per CU, so one's epilogue overlaps the other's main loop) wins
-  // for narrow or short-K products.  Thresholds from timings of the workload shapes.
+  // needs several rounds of tiles per CU and wastes the ragged part of N; 256x192 takes
+  // over where N is a multiple of 192 that 256 would pad by more than 5 % (N = 1152:
+  // 11 % padding and 2.5 rounds of tiles become none and 3); 128x128 (4 waves, two
+  // workgroups per CU, so one's epilogue overlaps the other's main loop) wins for
+  // narrow or short-K products.  Thresholds from timings of the workload shapes.
   const long long tiles256 = (long long)ceil_div(M, 256) * ceil_div(N, 256);
   const double waste = (double)ceil_div(N, 256) * 256.0 / N - 1.0;
+  if (N % 192 == 0 && waste > 0.05 && (long long)ceil_div(M, 256) * (N / 192) >= 192)
+    return run_dlds<256, 192, 64, 4, 2, 2, MODE>(A, Wt, M, N, K, ep, s);
   if (tiles256 >= 600 && (waste <= 0.05 || K >= 2048)) return run_dlds<256, 256, 64, 4, 2, 2, MODE>(A, Wt, M, N, K, ep, s);
   return run_dlds<128, 128, 64, 2, 2, 2, MODE>(A, Wt, M, N, K, ep, s);
 }

@@ -22,7 +22,8 @@ def _torch():
 
 LIN_SHAPES = [
     (1, 32, 64), (300, 200, 128), (513, 384, 256), (64, 1152, 1152), (127, 96, 64),
-    (8209, 2048, 128),       # enough tiles for the 256x128 configuration, ragged M
+    (8209, 2048, 128),       # enough tiles for the 256x256 configuration, ragged M
+    (8200, 1152, 128),       # N a multiple of 192 that 256 would pad: the 256x192 configuration, ragged M
     (250, 160, 72),          # K not a multiple of 64: plain kernel
 ]
 
