@@ -95,7 +95,11 @@ def test_linear_gated_branch_then_residual_layernorm(fc, dtype, gated):
 
 # --------------------------------------------------------------------------- attention
 
-def _attn_case(fc, G, nq, nk, d, gain, bf, impl):
+def _attn_case(fc, G, nq, nk, d, gain, bf, impl, scaled_q_rounding=False):
+    """scaled_q_rounding: the MFMA flash kernel consumes bf16(q * scale * log2 e) (inside a
+    step the QKV epilogue produces exactly that from fp32; the stand-alone operator has to
+    round its bf16 input a second time).  The oracle is then fed that same rounded query,
+    so the comparison measures the kernel's arithmetic and not the input conversion."""
     torch = _torch()
     qs, ks, vs = [], [], []
     for g in range(G):
@@ -104,7 +108,11 @@ def _attn_case(fc, G, nq, nk, d, gain, bf, impl):
     q, k, v = np.stack(qs), np.stack(ks), np.stack(vs)
     if bf:
         q, k, v = BF(q), BF(k), BF(v)
-    want = dit.attention(q.astype(np.float64), k.astype(np.float64), v.astype(np.float64))
+    q_seen = q
+    if scaled_q_rounding:
+        c = np.float32(1.4426950408889634 / math.sqrt(d))
+        q_seen = BF(q.astype(np.float32) * c).astype(np.float64) / np.float64(c)
+    want = dit.attention(np.asarray(q_seen, dtype=np.float64), k.astype(np.float64), v.astype(np.float64))
     out = torch.full((G, nq, d), float("nan"), dtype=torch.bfloat16 if bf else torch.float32, device="cuda:0")
     fc.fc_op_attention(fc.FC_BF16 if bf else fc.FC_F32, dev(q, bf), dev(k, bf), dev(v, bf), out, G, nq, nk, d, impl)
     torch.cuda.synchronize()
@@ -113,13 +121,14 @@ def _attn_case(fc, G, nq, nk, d, gain, bf, impl):
 
 @pytest.mark.parametrize("G,nq,nk,d", [(3, 300, 333, 64), (2, 64, 64, 64), (1, 1, 1, 64), (2, 257, 120, 72),
                                        (1, 700, 1000, 64), (4, 256, 256, 72), (1, 33, 7, 72), (2, 600, 333, 64),
-                                       (1, 1100, 1000, 64), (2, 513, 129, 64)])
+                                       (1, 1100, 1000, 64), (2, 513, 129, 64),
+                                       (1, 4200, 650, 64)])      # long enough for the 8-wave workgroup, ragged both ways
 @pytest.mark.parametrize("gain", [1.0, 2.5])
 def test_attention_flash_bf16(fc, G, nq, nk, d, gain):
-    got, want = _attn_case(fc, G, nq, nk, d, gain, True, 0)
+    got, want = _attn_case(fc, G, nq, nk, d, gain, True, 0, scaled_q_rounding=True)
     assert np.all(np.isfinite(got))
-    assert rel_l2(got, want) < 1e-2, (rel_l2(got, want), max_abs(got, want))
-    assert max_abs(got, want) < 5e-2
+    assert rel_l2(got, want) < 4e-3, (rel_l2(got, want), max_abs(got, want))
+    assert max_abs(got, want) < 2.5e-2
 
 
 @pytest.mark.parametrize("G,nq,nk,d,bf", [(2, 50, 70, 16, False), (3, 16, 16, 72, True), (1, 100, 130, 64, True),
