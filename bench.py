@@ -59,7 +59,7 @@ def cpu_baseline(w, weights, lat, cond):
     if cfg.attn_mode == synth.ATTN_FULL3D_CONCAT and cfg.depth == 1:
         # evaluate n1 and 2*n1 sampled query rows; the cost is affine in the row count
         rng = np.random.default_rng(0)
-        n1 = 768
+        n1 = 2048                                # about 10 s of host work in all
         rows = rng.choice(cfg.video_tokens, size=2 * n1, replace=False)
         t0 = time.perf_counter(); dit.forward(cfg, W32, lat[0], cond[0], 500, dtype=None, video_rows=rows[:n1])
         t1 = time.perf_counter(); dit.forward(cfg, W32, lat[0], cond[0], 500, dtype=None, video_rows=rows)
@@ -72,9 +72,10 @@ def cpu_baseline(w, weights, lat, cond):
                   f"{cfg.seq_tokens} tokens), extrapolated affinely to {cfg.video_tokens} rows; measured "
                   f"{a:.1f}s + {b:.1f}s")
     else:
-        # one forward of one sample through min(depth, 2) blocks, scaled to depth and batch
+        # one forward of one sample (through at most 28 blocks: about 10 s at the 1152-wide
+        # shapes), scaled to depth and batch
         from dataclasses import replace
-        d = min(cfg.depth, 2)
+        d = min(cfg.depth, 28)
         cfg_s = replace(cfg, depth=d)
         Ws = {k: v for k, v in W32.items() if not k.startswith("blk") or int(k[3:k.index(".")]) < d}
         t0 = time.perf_counter(); dit.forward(cfg_s, Ws, lat[0].astype(np.float32), cond[0].astype(np.float32), 500,
@@ -184,6 +185,26 @@ def main():
     for k, f in per_launch_flops.items():
         if k in kernels:
             kernels[k]["tflops"] = f / (kernels[k]["avg_launch_ms"] * 1e-3) / 1e12
+    # HBM-bound launch groups: algorithmic bytes per step (what has to cross HBM once) over their time
+    esz = 2 if cfg.dtype == synth.DT_BF16 else 4
+    elems = forwards * cfg.seq_tokens * cfg.hidden
+    factorized = cfg.attn_mode == synth.ATTN_FACTORIZED_CROSS
+    ln_launches = (4 if factorized else 2) * cfg.depth + 1
+    nmod = 9 if factorized else 6
+    lat_elems = R * cfg.frames * cfg.height * cfg.width * cfg.channels
+    per_step_bytes = {
+        # x (fp32) in, out (act) out; every launch but the first also folds a branch in: + y in, x out
+        "ln_modulate": elems * ((4 + esz) + (ln_launches - 1) * (4 + esz + esz + 4)),
+        "patch_embed": forwards * cfg.video_tokens * cfg.hidden * 4,
+        "timestep_modulation": (cfg.depth * nmod + 2) * cfg.hidden * cfg.hidden * esz
+                               + (cfg.t_embed_dim + cfg.hidden) * cfg.hidden * esz,
+        "cfg_ddim": lat_elems * (16 if use_cfg else 12),
+        "attn_temporal": cfg.depth * 4 * forwards * cfg.video_tokens * cfg.hidden * esz,
+        "attn_cross": cfg.depth * 2 * forwards * cfg.video_tokens * cfg.hidden * esz,
+    }
+    for k, nbytes in per_step_bytes.items():
+        if k in kernels:
+            kernels[k]["gbps"] = nbytes / (kernels[k]["ms_per_step"] * 1e-3) / 1e9
     if dom in per_launch_flops:
         ach = per_launch_flops[dom] / (dom_launch_ms * 1e-3) / 1e12
         roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
