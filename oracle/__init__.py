@@ -1,2 +1,2 @@
 """Plain CPU oracle of the denoising path (test infrastructure, not product code)."""
-from . import dit, sampler  # noqa: F401
+from . import cache, dit, sampler  # noqa: F401
