@@ -88,6 +88,73 @@ def cpu_baseline(w, weights, lat, cond):
     return {"value": 1.0 / step_s, "unit": "steps/s", "cores": int(cores), "kind": "oracle", "sample": sample}
 
 
+def cache_restore_bench(args):
+    """Secondary measurement (--cache-restore): the entry points that produce the `latent`
+    argument of a resume, at the paper's latent shape (64 x 40 x 64 x 4, Sec. 2.3) and on a
+    batch of 256 such latents, where the HBM rate shows.  One JSON line."""
+    import torch
+    import paper_2501_04012_amd as fc
+    torch.cuda.set_device(0)
+    T, H, W, C = 64, 40, 64, 4
+    F = H * W * C
+    out = {}
+    for label, R in (("one_latent", 1), ("batch_256", 256)):
+        frames = R * T
+        g = torch.Generator(device="cuda").manual_seed(1)
+        xo = torch.randn(frames, H, W, C, device="cuda", generator=g)
+        xb = torch.randn(frames, H, W, C, device="cuda", generator=g)
+        # masks shaped like a segmented object: a rectangle per frame that drifts with the frame
+        # index; the background mask is its complement grown by one pixel (a slight misalignment)
+        obj = np.zeros((frames, H, W), dtype=bool)
+        bgm = np.ones((frames, H, W), dtype=bool)
+        for f in range(frames):
+            x0 = 8 + (f % T) // 4
+            obj[f, 10:30, x0:x0 + 24] = True
+            bgm[f, 9:31, x0 - 1:x0 + 25] = False
+        mo = torch.from_numpy(np.packbits(obj.reshape(-1), bitorder="little")).cuda()
+        mb = torch.from_numpy(np.packbits(bgm.reshape(-1), bitorder="little")).cuda()
+        dst = torch.empty_like(xo)
+
+        def timed(fn, reps=args.steps):
+            for _ in range(args.warmup):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        ms = timed(lambda: fc.fc_cache_stitch(xo, xb, mo, mb, dst, frames * H * W, C))
+        nbytes = frames * F * 4 * 2 + 2 * mo.numel()           # one source read and one write per element, both masks
+        res = {"stitch": {"ms": ms, "gbps": nbytes / ms / 1e6}}
+        if R == 1:
+            n_base, n_extra = 8, 4
+            src = [0] + [1 + (t % n_base) if t % 5 else -(1 + t % n_extra) for t in range(1, T)]
+            ms = timed(lambda: fc.fc_cache_decompress(xo[0], xb[:n_base], n_base, 0.75, xb[8:8 + n_extra], n_extra, src,
+                                                      T, F, dst))
+            reads = sum(2 if c > 0 else 1 for c in src)
+            res["decompress"] = {"ms": ms, "gbps": (reads + T) * F * 4 / ms / 1e6}
+            ws = torch.empty(fc.fc_cache_workspace_bytes(T), dtype=torch.uint8, device="cuda")
+            a = torch.zeros(1, device="cuda")
+            ms = timed(lambda: fc.fc_cache_alpha(xo[0], xo[1:1 + n_base], xb[:n_base], n_base, F, a, ws))
+            res["alpha"] = {"ms": ms, "gbps": (2 * n_base + 1) * F * 4 / ms / 1e6}
+            sim = torch.empty(T, T, device="cuda")
+            ms = timed(lambda: fc.fc_cache_frame_similarity(xo, T, F, sim, ws))
+            res["frame_similarity"] = {"ms": ms, "gbps": T * F * 4 / ms / 1e6}
+        out[label] = res
+    best = out["batch_256"]["stitch"]["gbps"]
+    print(json.dumps({
+        "metric": "cache restore (stitch) GB/s on 256 paper-shaped latents", "value": best, "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": out["batch_256"]["stitch"]["ms"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "cache_restore", "latent": [T, H, W, C]},
+        "roofline": {"kernel": "k_stitch", "bound": "hbm", "achieved": best, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                     "frac": best / PEAK_HBM_GBS, "traffic": None},
+        "ops": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -95,6 +162,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cache-restore", action="store_true",
+                    help="time the cache-restore entry points instead of a denoising workload")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this size (a known-size kernel for scaling HBM counters)")
     args = ap.parse_args()
@@ -110,6 +179,9 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
+    if args.cache_restore:
+        cache_restore_bench(args)
+        return
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]
     cfg = w.model

@@ -143,6 +143,18 @@ int fc_denoise_resume(fc_model* m, float* latent, const float* cond, const float
                       const fc_schedule* sched, int32_t k, int32_t batch_requests,
                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* fc_denoise_resume that also hands out intermediate latents: after step export_steps[e]
+ * (ascending, each in k+1 .. N; host array) the latents of all R requests are copied to
+ * export_dst[e] (host array of dev pointers, each R*T*H*W*C floats) in stream order, without
+ * a host wait.  These are the latents a cache inserts for the key steps between the step
+ * that was hit and the last cached step (Sec. 4.2.4 "Cache Operations", Insertion).
+ * n_export = 0 is fc_denoise_resume.  Errors as fc_denoise_resume, FC_ERR_RANGE for steps
+ * outside k+1 .. N or not ascending. */
+int fc_denoise_resume_ex(fc_model* m, float* latent, const float* cond, const float* null_cond,
+                         const fc_schedule* sched, int32_t k, int32_t batch_requests,
+                         int32_t n_export, const int32_t* export_steps, float* const* export_dst,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* The four DDIM coefficients of a step, as the kernels receive them (computed in
  * double, rounded to float): out4 = { sqrt(abar_t), sqrt(1-abar_t), sqrt(abar_prev),
  * sqrt(1-abar_prev) }, *t_out = training timestep of the step.  Host only. */
@@ -164,6 +176,50 @@ int fc_profile_select(fc_model* m, int32_t category);
 int fc_profile_categories(void);
 const char* fc_profile_category_name(int32_t i);
 int fc_profile_read(fc_model* m, int32_t n, double* ms_out, int64_t* launches_out);
+
+/* ---- restoring a cached latent: what produces the `latent` argument of a resume.
+ * Latents are f32 [frames, H, W, C]; a "frame" below is its H*W*C = frame_elems floats. */
+
+/* Stitching of a decoupled hit (Sec. 4.2.2 "Video Latent Reconstruction"): out takes a
+ * pixel (all `channels` values) from x_obj where the object mask is set or the background
+ * mask is clear, else from x_bg.  Masks (dev): 1 bit per pixel, pixel i in bit i % 8 of
+ * byte i / 8, (pixels + 7) / 8 bytes; m_bg NULL = background valid everywhere.  out may
+ * be x_obj or x_bg itself.  All pointers dev. */
+int fc_cache_stitch(const float* x_obj, const float* x_bg, const uint8_t* m_obj, const uint8_t* m_bg,
+                    float* out, int64_t pixels, int32_t channels, void* hip_stream);
+
+/* Expanding a compressed entry of one step (Sec. 4.1.1 decompression, Sec. 4.1.2 Eq. 1,
+ * Sec. 4.3 "Cache Entry Structure"): out[t] (dev, frames x frame_elems) is built from
+ * source code src[t] (host array): 0 = first (the stored first frame of the step);
+ * j in 1..n_base = first + alpha * diff_base[j-1] (a common key frame); -(e+1) =
+ * extra[e] (a key frame stored whole).  Repeated key frames are repeated codes.
+ * first, diff_base [n_base, frame_elems], extra [n_extra, frame_elems], out: dev.
+ * At most 256 frames (FC_ERR_UNSUPPORTED); FC_ERR_RANGE for a code outside the entry. */
+int fc_cache_decompress(const float* first, const float* diff_base, int32_t n_base, float alpha,
+                        const float* extra, int32_t n_extra, const int32_t* src, int32_t frames,
+                        int64_t frame_elems, float* out, void* hip_stream);
+
+/* Bytes of device workspace (8-byte aligned) for the two reductions below. */
+size_t fc_cache_workspace_bytes(int32_t frames);
+
+/* The coefficient of Eq. 2 (Sec. 4.1.2): alpha_out[0] (dev) = sum((keys_s - first_s) *
+ * diff_base) / sum(diff_base^2) over n_base frames; first_s [frame_elems], keys_s and
+ * diff_base [n_base, frame_elems], all dev.  Sums in double, fixed order (bitwise
+ * repeatable). */
+int fc_cache_alpha(const float* first_s, const float* keys_s, const float* diff_base, int32_t n_base,
+                   int64_t frame_elems, float* alpha_out, void* workspace, size_t workspace_bytes,
+                   void* hip_stream);
+
+/* sim [frames, frames] (dev, f32) = cosine similarity of every pair of frames of
+ * frames_dev [frames, frame_elems] (Sec. 4.1.1; Sec. 5 "Cache compressor"). */
+int fc_cache_frame_similarity(const float* frames_dev, int32_t frames, int64_t frame_elems, float* sim,
+                              void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Key-frame choice of Sec. 4.1.1 on a host copy of sim: frames are visited from the last
+ * to the first; an unassigned frame becomes a key frame and every unassigned frame in
+ * front of it with sim >= threshold is mapped to it.  map_out[f] (host) = the key frame
+ * standing for frame f.  Host only. */
+int fc_cache_select_key_frames(const float* sim, int32_t frames, float threshold, int32_t* map_out);
 
 /* ---- single operators of the step, exposed for per-kernel tests and timing.
  * All pointers dev; dtype FC_F32 -> float elements, FC_BF16 -> bfloat16 (uint16)

@@ -51,7 +51,17 @@ EXPORTS = {
                         C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
     "fc_denoise_resume": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(fc_schedule), C.c_int32,
                           C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p],
+    "fc_denoise_resume_ex": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(fc_schedule), C.c_int32,
+                             C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_void_p), C.c_void_p, C.c_size_t,
+                             C.c_void_p],
     "fc_schedule_coefficients": [C.POINTER(fc_schedule), C.c_int32, C.POINTER(C.c_float), C.POINTER(C.c_int32)],
+    "fc_cache_stitch": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p],
+    "fc_cache_decompress": [C.c_void_p, C.c_void_p, C.c_int32, C.c_float, C.c_void_p, C.c_int32,
+                            C.POINTER(C.c_int32), C.c_int32, C.c_int64, C.c_void_p, C.c_void_p],
+    "fc_cache_alpha": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t,
+                       C.c_void_p],
+    "fc_cache_frame_similarity": [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
+    "fc_cache_select_key_frames": [C.POINTER(C.c_float), C.c_int32, C.c_float, C.POINTER(C.c_int32)],
     "fc_profile_enable": [C.c_void_p, C.c_int32],
     "fc_profile_select": [C.c_void_p, C.c_int32],
     "fc_profile_categories": [],
@@ -69,6 +79,7 @@ EXPORTS = {
                        C.POINTER(C.c_float), C.c_void_p],
 }
 _STRING_EXPORTS = {"fc_status_string": [C.c_int], "fc_last_error": [], "fc_profile_category_name": [C.c_int32]}
+_SIZE_EXPORTS = {"fc_cache_workspace_bytes": [C.c_int32]}
 
 
 def _load():
@@ -82,6 +93,9 @@ def _load():
     for name, argtypes in _STRING_EXPORTS.items():
         fn = getattr(lib, name)
         fn.argtypes, fn.restype = argtypes, C.c_char_p
+    for name, argtypes in _SIZE_EXPORTS.items():
+        fn = getattr(lib, name)
+        fn.argtypes, fn.restype = argtypes, C.c_size_t
     return lib
 
 
@@ -164,6 +178,56 @@ def fc_denoise_resume(model, latent, cond, null_cond, sched: synth.Schedule, k: 
     _check(_lib.fc_denoise_resume(model, _ptr(latent), _ptr(cond), _ptr(null_cond), C.byref(s), k, batch_requests,
                                   _ptr(workspace), workspace.numel() * workspace.element_size(),
                                   _stream(stream)), "fc_denoise_resume")
+
+
+def fc_denoise_resume_ex(model, latent, cond, null_cond, sched: synth.Schedule, k: int, batch_requests: int,
+                         export_steps, export_dst, workspace, stream=None) -> None:
+    """export_steps: ascending step numbers; export_dst: device tensors of the latent's size."""
+    s = _sched_struct(sched)
+    n = len(export_steps)
+    steps = (C.c_int32 * max(n, 1))(*[int(v) for v in export_steps])
+    dsts = (C.c_void_p * max(n, 1))(*[_ptr(t) for t in export_dst])
+    _check(_lib.fc_denoise_resume_ex(model, _ptr(latent), _ptr(cond), _ptr(null_cond), C.byref(s), k, batch_requests,
+                                     n, steps, dsts, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                     _stream(stream)), "fc_denoise_resume_ex")
+
+
+def fc_cache_stitch(x_obj, x_bg, m_obj, m_bg, out, pixels: int, channels: int, stream=None) -> None:
+    _check(_lib.fc_cache_stitch(_ptr(x_obj), _ptr(x_bg), _ptr(m_obj), _ptr(m_bg), _ptr(out), pixels, channels,
+                                _stream(stream)), "fc_cache_stitch")
+
+
+def fc_cache_decompress(first, diff_base, n_base: int, alpha: float, extra, n_extra: int, src, frames: int,
+                        frame_elems: int, out, stream=None) -> None:
+    codes = (C.c_int32 * max(frames, 1))(*[int(v) for v in src])
+    _check(_lib.fc_cache_decompress(_ptr(first), _ptr(diff_base), n_base, alpha, _ptr(extra), n_extra, codes, frames,
+                                    frame_elems, _ptr(out), _stream(stream)), "fc_cache_decompress")
+
+
+def fc_cache_workspace_bytes(frames: int) -> int:
+    return int(_lib.fc_cache_workspace_bytes(frames))
+
+
+def fc_cache_alpha(first_s, keys_s, diff_base, n_base: int, frame_elems: int, alpha_out, workspace,
+                   stream=None) -> None:
+    _check(_lib.fc_cache_alpha(_ptr(first_s), _ptr(keys_s), _ptr(diff_base), n_base, frame_elems, _ptr(alpha_out),
+                               _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)),
+           "fc_cache_alpha")
+
+
+def fc_cache_frame_similarity(frames_dev, frames: int, frame_elems: int, sim, workspace, stream=None) -> None:
+    _check(_lib.fc_cache_frame_similarity(_ptr(frames_dev), frames, frame_elems, _ptr(sim), _ptr(workspace),
+                                          workspace.numel() * workspace.element_size(), _stream(stream)),
+           "fc_cache_frame_similarity")
+
+
+def fc_cache_select_key_frames(sim_host: np.ndarray, threshold: float = 0.99) -> np.ndarray:
+    sim_host = np.ascontiguousarray(sim_host, dtype=np.float32)
+    T = sim_host.shape[0]
+    out = (C.c_int32 * max(T, 1))()
+    _check(_lib.fc_cache_select_key_frames(sim_host.ctypes.data_as(C.POINTER(C.c_float)), T, threshold, out),
+           "fc_cache_select_key_frames")
+    return np.array(out[:T], dtype=np.int64)
 
 
 def fc_schedule_coefficients(sched: synth.Schedule, step: int):
@@ -257,6 +321,10 @@ class Denoiser:
     def resume(self, latent, cond, null_cond, sched, k, stream=None):
         fc_denoise_resume(self.model, latent, cond, null_cond if self.use_cfg else None, sched, k, self.R,
                           self.workspace, stream)
+
+    def resume_ex(self, latent, cond, null_cond, sched, k, export_steps, export_dst, stream=None):
+        fc_denoise_resume_ex(self.model, latent, cond, null_cond if self.use_cfg else None, sched, k, self.R,
+                             export_steps, export_dst, self.workspace, stream)
 
     def close(self):
         if self.model:

@@ -257,4 +257,16 @@ hipError_t launch_gemm(int bf16, int mode, const void* A, const void* Wt, int M,
                        const EpiParams& ep, hipStream_t s);
 hipError_t launch_attention(int bf16, const AttnParams& p, int impl, hipStream_t s);
 
+// cache restore (cache.hip)
+constexpr int kMaxCacheFrames = 256;     // frames of one entry (source codes travel as a kernel argument)
+constexpr size_t kCacheReduceWsBytes = 256 * 2 * sizeof(double);
+hipError_t launch_stitch(const float* x_obj, const float* x_bg, const uint8_t* m_obj, const uint8_t* m_bg, float* out,
+                         long long pixels, int channels, hipStream_t s);
+hipError_t launch_decompress(const float* first, const float* diff_base, float alpha, const float* extra,
+                             const int* src_host, int T, long long F, float* out, hipStream_t s);
+hipError_t launch_alpha(const float* first_s, const float* keys_s, const float* diff_base, int n_base, long long F,
+                        float* alpha_out, double* ws, hipStream_t s);
+hipError_t launch_frame_similarity(const float* frames, int T, long long F, float* sim, double* ws, hipStream_t s);
+hipError_t launch_copy_f32(const float* in, float* out, size_t n, hipStream_t s);
+
 }  // namespace fc

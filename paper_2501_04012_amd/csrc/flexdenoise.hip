@@ -653,18 +653,43 @@ int fc_denoise_step(fc_model* m, float* latent, const float* cond, const float* 
   return run_step(ctx, latent, sched, step, eps_out);
 }
 
-int fc_denoise_resume(fc_model* m, float* latent, const float* cond, const float* null_cond,
-                      const fc_schedule* sched, int32_t k, int32_t R, void* workspace, size_t workspace_bytes,
-                      void* stream) {
+int fc_denoise_resume_ex(fc_model* m, float* latent, const float* cond, const float* null_cond,
+                         const fc_schedule* sched, int32_t k, int32_t R, int32_t n_export,
+                         const int32_t* export_steps, float* const* export_dst, void* workspace,
+                         size_t workspace_bytes, void* stream) {
   Ctx ctx;
   int rc = check_call(m, latent, cond, sched, R, workspace, workspace_bytes, null_cond != nullptr, &ctx, stream);
   if (rc != FC_OK) return rc;
   if (k < 0 || k > sched->num_steps) return fail(FC_ERR_RANGE, "k must be in 0..num_steps");
+  if (n_export < 0) return fail(FC_ERR_RANGE, "n_export is negative");
+  if (n_export > 0 && (!export_steps || !export_dst)) return fail(FC_ERR_NULL, "export arrays are NULL");
+  for (int e = 0; e < n_export; ++e) {
+    if (export_steps[e] <= k || export_steps[e] > sched->num_steps)
+      return fail(FC_ERR_RANGE, "export steps must lie in k+1..num_steps");
+    if (e > 0 && export_steps[e] <= export_steps[e - 1]) return fail(FC_ERR_RANGE, "export steps must ascend");
+    if (!export_dst[e]) return fail(FC_ERR_NULL, "export destination is NULL");
+  }
   if (k == sched->num_steps) return FC_OK;
   if ((rc = prepare(ctx, cond, null_cond)) != FC_OK) return rc;
-  for (int s = k + 1; s <= sched->num_steps; ++s)
+  const fc_model_config& cf = m->cfg;
+  const size_t lat_elems = (size_t)R * cf.frames * cf.height * cf.width * cf.channels;
+  int next = 0;
+  for (int s = k + 1; s <= sched->num_steps; ++s) {
     if ((rc = run_step(ctx, latent, sched, s, nullptr)) != FC_OK) return rc;
+    if (next < n_export && export_steps[next] == s) {
+      // stream-ordered device copy: the next step reads the latent after it, nothing waits on the host
+      HIP_TRY(launch_copy_f32(latent, export_dst[next], lat_elems, ctx.s));
+      ++next;
+    }
+  }
   return FC_OK;
+}
+
+int fc_denoise_resume(fc_model* m, float* latent, const float* cond, const float* null_cond,
+                      const fc_schedule* sched, int32_t k, int32_t R, void* workspace, size_t workspace_bytes,
+                      void* stream) {
+  return fc_denoise_resume_ex(m, latent, cond, null_cond, sched, k, R, 0, nullptr, nullptr, workspace, workspace_bytes,
+                              stream);
 }
 
 int fc_schedule_coefficients(const fc_schedule* sched, int32_t step, float* out4, int32_t* t_out) {
@@ -774,6 +799,70 @@ int fc_op_patch_embed(const float* latent, int32_t R, int32_t B, const float* Wp
     return fail(FC_ERR_UNSUPPORTED, "the matrix-core patch embedding needs p = 2, C = 16, D % 256 = 0");
   HIP_TRY(launch_patch_embed(latent, R, B, Wp, bp, pos_sp, pos_t, x, T, H, W, C, p, D, rows_per_b, row_off, impl,
                              (hipStream_t)stream));
+  return FC_OK;
+}
+
+// ---------------------------------------------------------------- restoring a cached latent
+int fc_cache_stitch(const float* x_obj, const float* x_bg, const uint8_t* m_obj, const uint8_t* m_bg, float* out,
+                    int64_t pixels, int32_t channels, void* stream) {
+  if (!x_obj || !x_bg || !m_obj || !out) return fail(FC_ERR_NULL, "NULL argument");
+  if (pixels < 0 || channels < 1) return fail(FC_ERR_RANGE, "bad pixel or channel count");
+  HIP_TRY(launch_stitch(x_obj, x_bg, m_obj, m_bg, out, pixels, channels, (hipStream_t)stream));
+  return FC_OK;
+}
+
+int fc_cache_decompress(const float* first, const float* diff_base, int32_t n_base, float alpha, const float* extra,
+                        int32_t n_extra, const int32_t* src, int32_t frames, int64_t frame_elems, float* out,
+                        void* stream) {
+  if (!first || !src || !out) return fail(FC_ERR_NULL, "NULL argument");
+  if (n_base < 0 || n_extra < 0 || frames < 0 || frame_elems < 0) return fail(FC_ERR_RANGE, "negative size");
+  if (frames > kMaxCacheFrames) return fail(FC_ERR_UNSUPPORTED, "more than 256 frames in one entry");
+  if ((n_base > 0 && !diff_base) || (n_extra > 0 && !extra)) return fail(FC_ERR_NULL, "NULL frame array");
+  for (int t = 0; t < frames; ++t)
+    if (src[t] > n_base || src[t] < -n_extra) return fail(FC_ERR_RANGE, "source code names a frame the entry does not hold");
+  HIP_TRY(launch_decompress(first, diff_base, alpha, extra, src, frames, frame_elems, out, (hipStream_t)stream));
+  return FC_OK;
+}
+
+size_t fc_cache_workspace_bytes(int32_t frames) {
+  const size_t gram = (size_t)(frames > 0 ? frames : 0) * (size_t)(frames > 0 ? frames : 0) * sizeof(double);
+  return gram > kCacheReduceWsBytes ? gram : kCacheReduceWsBytes;
+}
+
+int fc_cache_alpha(const float* first_s, const float* keys_s, const float* diff_base, int32_t n_base,
+                   int64_t frame_elems, float* alpha_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!first_s || !keys_s || !diff_base || !alpha_out || !workspace) return fail(FC_ERR_NULL, "NULL argument");
+  if (n_base < 1 || frame_elems < 1) return fail(FC_ERR_RANGE, "needs at least one base frame");
+  if (workspace_bytes < kCacheReduceWsBytes || ((uintptr_t)workspace & 7))
+    return fail(FC_ERR_WORKSPACE, "workspace smaller than fc_cache_workspace_bytes() or misaligned");
+  HIP_TRY(launch_alpha(first_s, keys_s, diff_base, n_base, frame_elems, alpha_out, (double*)workspace,
+                       (hipStream_t)stream));
+  return FC_OK;
+}
+
+int fc_cache_frame_similarity(const float* frames_dev, int32_t frames, int64_t frame_elems, float* sim, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  if (!frames_dev || !sim || !workspace) return fail(FC_ERR_NULL, "NULL argument");
+  if (frames < 0 || frame_elems < 1) return fail(FC_ERR_RANGE, "bad frame count or size");
+  if (frames > kMaxCacheFrames) return fail(FC_ERR_UNSUPPORTED, "more than 256 frames in one entry");
+  if (workspace_bytes < fc_cache_workspace_bytes(frames) || ((uintptr_t)workspace & 7))
+    return fail(FC_ERR_WORKSPACE, "workspace smaller than fc_cache_workspace_bytes() or misaligned");
+  HIP_TRY(launch_frame_similarity(frames_dev, frames, frame_elems, sim, (double*)workspace, (hipStream_t)stream));
+  return FC_OK;
+}
+
+int fc_cache_select_key_frames(const float* sim, int32_t frames, float threshold, int32_t* map_out) {
+  if (!sim || !map_out) return fail(FC_ERR_NULL, "NULL argument");
+  if (frames < 0) return fail(FC_ERR_RANGE, "negative frame count");
+  for (int f = 0; f < frames; ++f) map_out[f] = -1;
+  // from the last frame to the first: an unassigned frame becomes a key frame and takes
+  // every unassigned frame in front of it that is similar enough
+  for (int f = frames - 1; f >= 0; --f) {
+    if (map_out[f] >= 0) continue;
+    map_out[f] = f;
+    for (int g = 0; g < f; ++g)
+      if (map_out[g] < 0 && sim[(size_t)f * frames + g] >= threshold) map_out[g] = f;
+  }
   return FC_OK;
 }
 

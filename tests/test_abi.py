@@ -8,6 +8,7 @@ import ctypes
 import numpy as np
 import pytest
 
+from oracle import cache as ocache
 from oracle import sampler
 from paper_2501_04012_amd import synth
 
@@ -72,3 +73,20 @@ def test_flop_accounting_matches_hand_counts():
     f4 = synth.forward_flops(synth.WORKLOADS["cfg4"].model)
     assert abs(f4["block_attention"] - 3.883e12) / 3.883e12 < 1e-3
     assert abs(f4["block_gemm"] + f4["block_attention"] - 7.91e12) / 7.91e12 < 2e-3
+
+
+def test_key_frame_selection_matches_oracle(fc):
+    """fc_cache_select_key_frames is host logic: same maps as the oracle on random and on
+    constructed similarity matrices, thresholds 0.9 and 0.99."""
+    rng = np.random.default_rng(3)
+    base = rng.standard_normal((5, 6, 6, 4))
+    for T in (1, 2, 7, 24, 64):
+        frames = np.stack([base[rng.integers(5)] + 0.06 * rng.standard_normal((6, 6, 4)) for _ in range(T)])
+        sim = ocache.frame_similarity(frames).astype(np.float32)
+        for thr in (0.9, 0.99):
+            want = ocache.select_key_frames(sim, np.float32(thr))
+            got = fc.fc_cache_select_key_frames(sim, thr)
+            assert np.array_equal(got, want), (T, thr)
+    chain = np.array([[1.0, 0.995, 0.98], [0.995, 1.0, 0.995], [0.98, 0.995, 1.0]], dtype=np.float32)
+    assert np.array_equal(fc.fc_cache_select_key_frames(chain, 0.99), [0, 2, 2])
+    assert fc.fc_cache_workspace_bytes(0) >= 4096 and fc.fc_cache_workspace_bytes(64) >= 64 * 64 * 8
