@@ -22,6 +22,16 @@ Readings the paper leaves open, as taken here:
   * classifier-free guidance: eps = eps_u + s (eps_c - eps_u), eps_u from a given
     'null' text embedding.
 
+A second step function, as a variant (sched.sampler = 1): the Euler step of a
+rectified-flow sampler.  The paper fixes only that the steps are sequential and that a
+hit continues with the very same step function (Sec. 2.1, Sec. 2.2), so the resume loop
+is the same; what changes is the update.  The network output is read as the velocity
+v = noise - x0 of the straight path x_sigma = (1 - sigma) x0 + sigma noise; sigma runs
+over the uniform grid sigma_j = j / N from 1 down to 0; step s (1-based) goes from
+sigma_{N-s+1} to sigma_{N-s} with x <- x + (sigma_{N-s} - sigma_{N-s+1}) v and the
+network is evaluated at t = sigma_{N-s+1} * train_steps.  Guidance combines velocities
+the way it combines eps.
+
 Pins (tests/test_oracle_sampler.py): closed-form schedule values, monotonicity,
 exact recovery x_prev = sqrt(abar_prev) x0 + sqrt(1-abar_prev) eps* when the
 network returns the true eps*, eps = 0 scaling, guidance special cases (s = 0,
@@ -62,6 +72,20 @@ def step_coefficients(sched, step):
     return t, float(abar[t]), abar_prev
 
 
+def flow_step_sigmas(sched, step):
+    """(t, sigma, sigma_next) of the step-th (1-based) Euler step on the uniform sigma grid."""
+    N = sched.num_steps
+    if not 1 <= step <= N:
+        raise ValueError("step out of range")
+    sigma, sigma_next = (N - step + 1) / N, (N - step) / N
+    return sigma * sched.train_steps, sigma, sigma_next
+
+
+def flow_euler_update(x, v, sigma, sigma_next):
+    """x_{sigma_next} = x_sigma + (sigma_next - sigma) v."""
+    return x + (sigma_next - sigma) * v
+
+
 def guide(eps_cond, eps_null, scale):
     """Classifier-free guidance: eps_u + s (eps_c - eps_u)."""
     return eps_null + scale * (eps_cond - eps_null)
@@ -84,7 +108,11 @@ def denoise_step(cfg, weights, latent, cond, null_cond, sched, step, dtype=np.fl
     Returns the latents after the step, same shape, in `dtype`."""
     if sched.eta != 0.0:
         raise ValueError("only the deterministic sampler (eta = 0) is defined here")
-    t, abar_t, abar_prev = step_coefficients(sched, step)
+    flow = getattr(sched, "sampler", 0) == 1
+    if flow:
+        t, sigma, sigma_next = flow_step_sigmas(sched, step)
+    else:
+        t, abar_t, abar_prev = step_coefficients(sched, step)
     if eps_fn is None:
         W = {k: np.asarray(v, dtype=dtype) for k, v in weights.items()}
         eps_fn = lambda x, txt, tt: dit.forward(cfg, W, x, txt, tt, dtype=None)
@@ -97,7 +125,7 @@ def denoise_step(cfg, weights, latent, cond, null_cond, sched, step, dtype=np.fl
             eps_u = eps_fn(lat[r], np.asarray(null_cond, dtype=dtype), t)
             eps = guide(eps, eps_u, sched.guidance_scale)
         eps_out[r] = eps
-        out[r] = ddim_update(lat[r], eps, abar_t, abar_prev)
+        out[r] = flow_euler_update(lat[r], eps, sigma, sigma_next) if flow else ddim_update(lat[r], eps, abar_t, abar_prev)
     return (out, eps_out) if return_eps else out
 
 

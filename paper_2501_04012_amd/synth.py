@@ -67,6 +67,10 @@ class ModelConfig:
         return self.hidden // self.heads
 
 
+SAMPLER_DDIM = 0          # eps-prediction, deterministic DDIM update
+SAMPLER_FLOW_EULER = 1    # velocity prediction, Euler step on sigma = 1 .. 0
+
+
 @dataclass(frozen=True)
 class Schedule:
     train_steps: int = 1000
@@ -75,6 +79,7 @@ class Schedule:
     num_steps: int = 50
     guidance_scale: float = 7.5
     eta: float = 0.0
+    sampler: int = 0          # SAMPLER_DDIM or SAMPLER_FLOW_EULER
 
 
 @dataclass(frozen=True)

@@ -141,3 +141,61 @@ def test_step_with_real_network_composes_forward_guidance_update():
         np.testing.assert_allclose(eps[r], e, atol=1e-13)
         x0 = (lat[r] - math.sqrt(1 - ab[500]) * e) / math.sqrt(ab[500])
         np.testing.assert_allclose(out[r], math.sqrt(ab[480]) * x0 + math.sqrt(1 - ab[480]) * e, atol=1e-12)
+
+
+# --------------------------------------------------------------------------- Euler step of a rectified-flow sampler (variant)
+
+def _flow_sched(n=50):
+    from dataclasses import replace
+    return replace(synth.Schedule(num_steps=n), sampler=synth.SAMPLER_FLOW_EULER)
+
+
+def test_flow_sigmas_cover_one_to_zero():
+    sched = _flow_sched(50)
+    t1, s1, n1 = sampler.flow_step_sigmas(sched, 1)
+    assert (t1, s1) == (1000.0, 1.0) and abs(n1 - 0.98) < 1e-15
+    tN, sN, nN = sampler.flow_step_sigmas(sched, 50)
+    assert abs(tN - 20.0) < 1e-12 and nN == 0.0
+    prev = None
+    for s in range(1, 51):
+        t, a, b = sampler.flow_step_sigmas(sched, s)
+        assert abs((a - b) - 1 / 50) < 1e-15 and abs(t - 1000 * a) < 1e-9
+        assert prev is None or abs(prev - a) < 1e-15          # steps chain: sigma_next of one is sigma of the next
+        prev = b
+
+
+def test_flow_true_velocity_lands_on_the_straight_path_and_ends_at_x0():
+    rng = np.random.default_rng(0)
+    x0, noise = rng.standard_normal((1, 3, 4, 4, 2)), rng.standard_normal((1, 3, 4, 4, 2))
+    v = noise - x0
+    sched = _flow_sched(10)
+    x = noise.copy()                                           # sigma = 1
+    for s in range(1, 11):
+        _, sig, nxt = sampler.flow_step_sigmas(sched, s)
+        assert np.allclose(x, (1 - sig) * x0 + sig * noise)
+        x = sampler.denoise_step(None, None, x, np.zeros((1, 1, 1)), None, sched, s, eps_fn=lambda a, b, t: v[0])
+    assert np.allclose(x, x0)
+
+
+def test_flow_step_dispatch_guidance_and_resume_composition():
+    rng = np.random.default_rng(1)
+    lat = rng.standard_normal((1, 2, 4, 4, 2))
+    sched = _flow_sched(8)
+    calls = []
+
+    def net(x, txt, t):
+        calls.append(t)
+        return 0.3 * x + float(txt.sum()) + 0.001 * t
+
+    cond, null = np.ones((1, 2, 3)), np.zeros((2, 3))
+    got = sampler.denoise_step(None, None, lat, cond, null, sched, 3, eps_fn=net)
+    t, sig, nxt = sampler.flow_step_sigmas(sched, 3)
+    vc, vu = 0.3 * lat[0] + 6.0 + 0.001 * t, 0.3 * lat[0] + 0.001 * t
+    want = lat[0] + (nxt - sig) * (vu + sched.guidance_scale * (vc - vu))
+    assert np.allclose(got[0], want) and calls == [t, t]
+    whole = sampler.denoise_resume(None, None, lat, cond, null, sched, 2, eps_fn=net)
+    part = sampler.denoise_resume(None, None, lat, cond, null, sched, 2, eps_fn=net, on_step=None)
+    mid = lat
+    for s in range(3, 9):
+        mid = sampler.denoise_step(None, None, mid, cond, null, sched, s, eps_fn=net)
+    assert np.allclose(whole, mid) and np.allclose(whole, part)
