@@ -71,16 +71,25 @@ typedef struct {
   float ln_eps;      /* LayerNorm epsilon (affine-free, biased variance) */
 } fc_model_config;
 
-/* Sampler.  beta_i linear from beta_start to beta_end over train_steps; the
- * num_steps sampling timesteps are tau_j = j*(train_steps/num_steps), visited in
- * descending order; step s (1-based) maps t = tau_{N-s} to tau_{N-s-1}, the last
- * step to abar_prev = 1.  eta must be 0. */
+/* Sampler.
+ * FC_SAMPLER_DDIM (eps-prediction): beta_i linear from beta_start to beta_end over
+ * train_steps; the num_steps sampling timesteps are tau_j = j*(train_steps/num_steps),
+ * visited in descending order; step s (1-based) maps t = tau_{N-s} to tau_{N-s-1}, the
+ * last step to abar_prev = 1.  eta must be 0.
+ * FC_SAMPLER_FLOW_EULER (variant; the network output is the velocity noise - x0 of the
+ * straight path x_sigma = (1 - sigma) x0 + sigma noise): sigma_j = j/N; step s goes from
+ * sigma_{N-s+1} to sigma_{N-s}, x <- x + (sigma_{N-s} - sigma_{N-s+1}) v, the network is
+ * evaluated at t = sigma_{N-s+1} * train_steps (train_steps % num_steps == 0 required);
+ * beta_* and eta are not used.  The resume loop is the same for both. */
+#define FC_SAMPLER_DDIM 0
+#define FC_SAMPLER_FLOW_EULER 1
 typedef struct {
   int32_t train_steps;
   float beta_start, beta_end;
   int32_t num_steps;
   float guidance_scale; /* used only when null_cond != NULL */
   float eta;
+  int32_t sampler;      /* FC_SAMPLER_* */
 } fc_schedule;
 
 /* Create a model for `cfg` on the current device.  *out receives the handle.
@@ -155,9 +164,11 @@ int fc_denoise_resume_ex(fc_model* m, float* latent, const float* cond, const fl
                          int32_t n_export, const int32_t* export_steps, float* const* export_dst,
                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* The four DDIM coefficients of a step, as the kernels receive them (computed in
- * double, rounded to float): out4 = { sqrt(abar_t), sqrt(1-abar_t), sqrt(abar_prev),
- * sqrt(1-abar_prev) }, *t_out = training timestep of the step.  Host only. */
+/* The four coefficients of a step, as the update kernel receives them (computed in
+ * double, rounded to float), for x0 = (x - c1 e) / c0, x <- c2 x0 + c3 e:
+ * DDIM: out4 = { sqrt(abar_t), sqrt(1-abar_t), sqrt(abar_prev), sqrt(1-abar_prev) };
+ * Euler: { 1, 0, 1, sigma_next - sigma }.  *t_out = timestep the network is evaluated
+ * at.  Host only. */
 int fc_schedule_coefficients(const fc_schedule* sched, int32_t step, float* out4, int32_t* t_out);
 
 const char* fc_status_string(int status);

@@ -107,6 +107,10 @@ int schedule_check(const fc_schedule* s) {
   if (s->eta != 0.0f) return fail(FC_ERR_UNSUPPORTED, "only the deterministic sampler (eta = 0) is implemented");
   if (s->train_steps < 1 || s->num_steps < 1 || s->num_steps > s->train_steps)
     return fail(FC_ERR_RANGE, "need 1 <= num_steps <= train_steps");
+  if (s->sampler != FC_SAMPLER_DDIM && s->sampler != FC_SAMPLER_FLOW_EULER)
+    return fail(FC_ERR_RANGE, "unknown sampler");
+  if (s->sampler == FC_SAMPLER_FLOW_EULER && s->train_steps % s->num_steps != 0)
+    return fail(FC_ERR_UNSUPPORTED, "the Euler sampler needs train_steps divisible by num_steps (integer timesteps)");
   return FC_OK;
 }
 
@@ -126,6 +130,14 @@ int step_coefficients(const fc_schedule* s, int step, float* out4, int* t_out) {
   const int N = s->num_steps;
   if (step < 1 || step > N) return fail(FC_ERR_RANGE, "step must be in 1..num_steps");
   const int stride = s->train_steps / N;
+  if (s->sampler == FC_SAMPLER_FLOW_EULER) {
+    // x <- x + (sigma_next - sigma) v on sigma_j = j / N, network evaluated at t = sigma * train_steps:
+    // in the update kernel's form x0 = (x - c1 e) / c0, x <- c2 x0 + c3 e that is (1, 0, 1, -1/N)
+    out4[0] = 1.0f; out4[1] = 0.0f; out4[2] = 1.0f;
+    out4[3] = (float)((double)(N - step) / N - (double)(N - step + 1) / N);
+    if (t_out) *t_out = (N - step + 1) * stride;
+    return FC_OK;
+  }
   const int t = (N - step) * stride;
   const double a_t = abar_at(s, t);
   const double a_p = step == N ? 1.0 : abar_at(s, (N - step - 1) * stride);

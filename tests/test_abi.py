@@ -45,6 +45,22 @@ def test_schedule_coefficients_match_oracle(fc):
     assert t == 0 and coef[2] == 1.0 and coef[3] == 0.0
 
 
+def test_flow_euler_coefficients_match_oracle(fc):
+    from dataclasses import replace
+    sched = replace(synth.Schedule(), sampler=synth.SAMPLER_FLOW_EULER)
+    for step in (1, 2, 25, 50):
+        coef, t = fc.fc_schedule_coefficients(sched, step)
+        ot, sig, nxt = sampler.flow_step_sigmas(sched, step)
+        assert t == ot
+        np.testing.assert_allclose(coef, [1.0, 0.0, 1.0, nxt - sig], rtol=1e-6, atol=0)
+    with pytest.raises(fc.FlexDenoiseError) as e:
+        fc.fc_schedule_coefficients(replace(sched, num_steps=30), 1)      # 1000 % 30 != 0
+    assert e.value.status == -6
+    with pytest.raises(fc.FlexDenoiseError) as e:
+        fc.fc_schedule_coefficients(replace(sched, sampler=7), 1)
+    assert e.value.status == -3
+
+
 def test_schedule_errors_are_status_codes(fc):
     from dataclasses import replace
     sched = synth.Schedule()

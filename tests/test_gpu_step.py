@@ -202,6 +202,35 @@ def test_cfg5b_resume_trajectory_and_invariants(fc):
         den.close()
 
 
+def test_flow_euler_variant_step_and_resume(fc):
+    """The second step function (Euler step of a rectified-flow sampler): one step of the
+    tiny fp32 configuration and of the bf16 factorized block, and a free-running tiny
+    resume, against the oracle."""
+    import torch
+    for name, bf in (("cfg1", False), ("cfg2", True)):
+        w = synth.WORKLOADS[name]
+        w = replace(w, schedule=replace(w.schedule, sampler=synth.SAMPLER_FLOW_EULER))
+        W = synth.make_weights(w.model, w.weight_seed)
+        inputs = synth.workload_inputs(w)
+        got = run_step_gpu(fc, w, weights=W, inputs=inputs)
+        want = oracle_step(w, w.model, W, inputs, w.step)
+        check(*got, *want, bf16=bf)
+    w = synth.WORKLOADS["cfg5b"]
+    sched = replace(w.schedule, sampler=synth.SAMPLER_FLOW_EULER)
+    W = synth.make_weights(w.model, w.weight_seed)
+    lat, cond, null = synth.workload_inputs(w)
+    den = fc.Denoiser(w.model, W, w.requests, True)
+    try:
+        d_lat = dev(lat)
+        den.resume(d_lat, dev(cond), dev(null), sched, 30)
+        torch.cuda.synchronize()
+        want = sampler.denoise_resume(w.model, W, lat, cond, null, sched, 30)
+        record(final_latent_rel_l2=rel_l2(host(d_lat), want))
+        assert rel_l2(host(d_lat), want) <= 1e-3
+    finally:
+        den.close()
+
+
 def test_api_errors(fc):
     import torch
     w = synth.WORKLOADS["cfg1"]
