@@ -18,7 +18,18 @@ Readings the paper leaves open, as taken here:
     in descending order; step s (1-based) goes from t = tau_{N-s} to tau_{N-s-1},
     and the last step goes to abar_prev = 1 (it returns the x0 estimate).
   * eta = 0: no noise is drawn, the update is a deterministic function of
-    (x_t, eps).
+    (x_t, eps).  eta > 0 (the paper changes the denoising seed after a retrieval to keep
+    outputs diverse, Appendix "Limitations"/discussion of homogenization, which needs a
+    sampler that draws noise): the DDIM family's stochastic member,
+      sigma = eta sqrt((1-abar_prev)/(1-abar_t)) sqrt(1 - abar_t/abar_prev),
+      x_prev = sqrt(abar_prev) x0 + sqrt(1 - abar_prev - sigma^2) eps + sigma z,
+    z standard normal.  z is not drawn from a stateful generator but computed from
+    (seed, request, step, element) with the counter-based Philox4x32-10 of Salmon et al.
+    (SC'11), so that any implementation produces the same noise: element i of request r
+    at step s takes lane i % 4 of the block with counter (i // 4 low word, i // 4 high
+    word, s, r) and key (seed low word, seed high word); a 32-bit output x becomes
+    u = ((x >> 8) + 0.5) 2^-24 in (0, 1); lanes (0, 1) and (2, 3) are Box-Muller pairs
+    (sqrt(-2 ln u_a) cos(2 pi u_b), sqrt(-2 ln u_a) sin(2 pi u_b)).
   * classifier-free guidance: eps = eps_u + s (eps_c - eps_u), eps_u from a given
     'null' text embedding.
 
@@ -31,6 +42,11 @@ over the uniform grid sigma_j = j / N from 1 down to 0; step s (1-based) goes fr
 sigma_{N-s+1} to sigma_{N-s} with x <- x + (sigma_{N-s} - sigma_{N-s+1}) v and the
 network is evaluated at t = sigma_{N-s+1} * train_steps.  Guidance combines velocities
 the way it combines eps.
+
+Pins of the noise path: the three published known-answer vectors of Philox4x32-10, the
+moments of the generated normals, eta = 0 equals the deterministic update, eta = 1
+equals the ancestral (posterior-variance) step, and the variance bookkeeping
+(1 - abar_prev - sigma^2) + sigma^2 = 1 - abar_prev.
 
 Pins (tests/test_oracle_sampler.py): closed-form schedule values, monotonicity,
 exact recovery x_prev = sqrt(abar_prev) x0 + sqrt(1-abar_prev) eps* when the
@@ -72,6 +88,53 @@ def step_coefficients(sched, step):
     return t, float(abar[t]), abar_prev
 
 
+# --------------------------------------------------------------------------- counter-based noise
+
+_PHILOX_M0, _PHILOX_M1 = np.uint64(0xD2511F53), np.uint64(0xCD9E8D57)
+_PHILOX_W0, _PHILOX_W1 = 0x9E3779B9, 0xBB67AE85
+
+
+def philox4x32_10(counter, key):
+    """counter [..., 4] and key [2] of 32-bit words -> [..., 4] uint32: ten rounds of
+    (hi(M0 c0), lo(M0 c0), hi(M1 c2), lo(M1 c2)) -> (hi1 ^ c1 ^ k0, lo1, hi0 ^ c3 ^ k1, lo0),
+    the key bumped by the Weyl constants between rounds."""
+    c = np.asarray(counter, dtype=np.uint64) & np.uint64(0xFFFFFFFF)
+    c0, c1, c2, c3 = c[..., 0], c[..., 1], c[..., 2], c[..., 3]
+    k0, k1 = int(key[0]) & 0xFFFFFFFF, int(key[1]) & 0xFFFFFFFF
+    mask = np.uint64(0xFFFFFFFF)
+    for _ in range(10):
+        p0, p1 = _PHILOX_M0 * c0, _PHILOX_M1 * c2
+        hi0, lo0, hi1, lo1 = p0 >> np.uint64(32), p0 & mask, p1 >> np.uint64(32), p1 & mask
+        c0, c1, c2, c3 = hi1 ^ c1 ^ np.uint64(k0), lo1, hi0 ^ c3 ^ np.uint64(k1), lo0
+        k0, k1 = (k0 + _PHILOX_W0) & 0xFFFFFFFF, (k1 + _PHILOX_W1) & 0xFFFFFFFF
+    return np.stack([c0, c1, c2, c3], axis=-1).astype(np.uint32)
+
+
+def counter_normals(seed, request, step, n):
+    """The n standard normals of (seed, request, step), float64."""
+    blocks = (n + 3) // 4
+    idx = np.arange(blocks, dtype=np.uint64)
+    ctr = np.stack([idx & np.uint64(0xFFFFFFFF), idx >> np.uint64(32),
+                    np.full(blocks, step, dtype=np.uint64), np.full(blocks, request, dtype=np.uint64)], axis=-1)
+    x = philox4x32_10(ctr, (seed & 0xFFFFFFFF, (seed >> 32) & 0xFFFFFFFF)).astype(np.float64)
+    u = (np.floor(x / 256.0) + 0.5) * 2.0 ** -24
+    z = np.empty((blocks, 4))
+    for a, b in ((0, 1), (2, 3)):
+        rad = np.sqrt(-2.0 * np.log(u[:, a]))
+        z[:, a], z[:, b] = rad * np.cos(2.0 * np.pi * u[:, b]), rad * np.sin(2.0 * np.pi * u[:, b])
+    return z.reshape(-1)[:n]
+
+
+def ddim_sigma(abar_t, abar_prev, eta):
+    return eta * math.sqrt((1.0 - abar_prev) / (1.0 - abar_t)) * math.sqrt(1.0 - abar_t / abar_prev)
+
+
+def ddim_update_stochastic(x_t, eps, abar_t, abar_prev, eta, z):
+    sigma = ddim_sigma(abar_t, abar_prev, eta)
+    x0 = (x_t - math.sqrt(1.0 - abar_t) * eps) / math.sqrt(abar_t)
+    return math.sqrt(abar_prev) * x0 + math.sqrt(max(1.0 - abar_prev - sigma * sigma, 0.0)) * eps + sigma * z
+
+
 def flow_step_sigmas(sched, step):
     """(t, sigma, sigma_next) of the step-th (1-based) Euler step on the uniform sigma grid."""
     N = sched.num_steps
@@ -106,9 +169,9 @@ def denoise_step(cfg, weights, latent, cond, null_cond, sched, step, dtype=np.fl
     latent [R,T,H,W,C]; cond [R,L,dt]; null_cond [L,dt] or None (no guidance).
     eps_fn(latent_r, text, t) replaces the network (used by the pins).
     Returns the latents after the step, same shape, in `dtype`."""
-    if sched.eta != 0.0:
-        raise ValueError("only the deterministic sampler (eta = 0) is defined here")
     flow = getattr(sched, "sampler", 0) == 1
+    if sched.eta != 0.0 and flow:
+        raise ValueError("eta belongs to the DDIM family; the Euler step draws no noise")
     if flow:
         t, sigma, sigma_next = flow_step_sigmas(sched, step)
     else:
@@ -125,7 +188,13 @@ def denoise_step(cfg, weights, latent, cond, null_cond, sched, step, dtype=np.fl
             eps_u = eps_fn(lat[r], np.asarray(null_cond, dtype=dtype), t)
             eps = guide(eps, eps_u, sched.guidance_scale)
         eps_out[r] = eps
-        out[r] = flow_euler_update(lat[r], eps, sigma, sigma_next) if flow else ddim_update(lat[r], eps, abar_t, abar_prev)
+        if flow:
+            out[r] = flow_euler_update(lat[r], eps, sigma, sigma_next)
+        elif sched.eta != 0.0:
+            z = counter_normals(getattr(sched, "seed", 0), r, step, lat[r].size).reshape(lat[r].shape)
+            out[r] = ddim_update_stochastic(lat[r], eps, abar_t, abar_prev, sched.eta, z)
+        else:
+            out[r] = ddim_update(lat[r], eps, abar_t, abar_prev)
     return (out, eps_out) if return_eps else out
 
 

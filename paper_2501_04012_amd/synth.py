@@ -80,6 +80,7 @@ class Schedule:
     guidance_scale: float = 7.5
     eta: float = 0.0
     sampler: int = 0          # SAMPLER_DDIM or SAMPLER_FLOW_EULER
+    seed: int = 0             # key of the counter-based noise drawn when eta > 0
 
 
 @dataclass(frozen=True)

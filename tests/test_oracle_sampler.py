@@ -123,8 +123,9 @@ def test_resume_semantics():
     assert len(fn4.calls) == 30
     with pytest.raises(ValueError):
         sampler.denoise_resume(cfg, None, x, cond, null, SCHED, 51, eps_fn=fn)
-    with pytest.raises(ValueError):
-        sampler.denoise_step(cfg, None, x, cond, null, replace(SCHED, eta=0.5), 1, eps_fn=fn)
+    with pytest.raises(ValueError):      # eta belongs to the DDIM family only
+        sampler.denoise_step(cfg, None, x, cond, null,
+                             replace(SCHED, eta=0.5, sampler=synth.SAMPLER_FLOW_EULER), 1, eps_fn=fn)
 
 
 def test_step_with_real_network_composes_forward_guidance_update():
@@ -199,3 +200,75 @@ def test_flow_step_dispatch_guidance_and_resume_composition():
     for s in range(3, 9):
         mid = sampler.denoise_step(None, None, mid, cond, null, sched, s, eps_fn=net)
     assert np.allclose(whole, mid) and np.allclose(whole, part)
+
+
+# --------------------------------------------------------------------------- eta > 0: counter-based noise
+
+def test_philox_known_answers():
+    """The known-answer vectors published with Philox4x32-10 (Random123, Salmon et al. SC'11)."""
+    kat = [
+        ((0, 0, 0, 0), (0, 0), (0x6627e8d5, 0xe169c58d, 0xbc57ac4c, 0x9b00dbd8)),
+        ((0xffffffff,) * 4, (0xffffffff, 0xffffffff), (0x408f276d, 0x41c83b0e, 0xa20bc7c6, 0x6d5451fd)),
+        ((0x243f6a88, 0x85a308d3, 0x13198a2e, 0x03707344), (0xa4093822, 0x299f31d0),
+         (0xd16cfe09, 0x94fdcceb, 0x5001e420, 0x24126ea1)),
+    ]
+    for ctr, key, want in kat:
+        got = sampler.philox4x32_10(np.array(ctr, dtype=np.uint64), key)
+        assert tuple(int(v) for v in got) == want
+    # vectorised evaluation equals one block at a time
+    ctrs = np.array([[1, 2, 3, 4], [5, 6, 7, 8]], dtype=np.uint64)
+    both = sampler.philox4x32_10(ctrs, (9, 10))
+    assert np.array_equal(both[1], sampler.philox4x32_10(ctrs[1], (9, 10)))
+
+
+def test_counter_normals_are_standard_normal_and_addressable():
+    z = sampler.counter_normals(1234, 0, 7, 200_003)
+    assert z.shape == (200_003,) and np.all(np.isfinite(z))
+    assert abs(z.mean()) < 0.01 and abs(z.var() - 1.0) < 0.01
+    assert abs(np.mean(z ** 3)) < 0.03 and abs(np.mean(z ** 4) - 3.0) < 0.06
+    assert abs(np.corrcoef(z[:-1], z[1:])[0, 1]) < 0.01
+    # a prefix is a prefix; another step, request or seed is another stream
+    assert np.array_equal(sampler.counter_normals(1234, 0, 7, 10), z[:10])
+    for other in ((1234, 0, 8), (1234, 1, 7), (1235, 0, 7), (1234 + (1 << 32), 0, 7)):
+        assert not np.allclose(sampler.counter_normals(*other, 10), z[:10])
+
+
+def test_stochastic_ddim_special_cases():
+    sched = synth.Schedule()
+    rng = np.random.default_rng(0)
+    x, eps, z = rng.standard_normal((3, 4)), rng.standard_normal((3, 4)), rng.standard_normal((3, 4))
+    t, a_t, a_p = sampler.step_coefficients(sched, 20)
+    # eta = 0 is the deterministic update
+    assert np.allclose(sampler.ddim_update_stochastic(x, eps, a_t, a_p, 0.0, z), sampler.ddim_update(x, eps, a_t, a_p))
+    # eta = 1: sigma^2 is the posterior variance (1-abar_prev)/(1-abar_t) * (1 - abar_t/abar_prev)
+    s1 = sampler.ddim_sigma(a_t, a_p, 1.0)
+    assert np.isclose(s1 ** 2, (1 - a_p) / (1 - a_t) * (1 - a_t / a_p))
+    # variance bookkeeping, and the last step draws nothing (abar_prev = 1)
+    for eta in (0.3, 1.0):
+        s = sampler.ddim_sigma(a_t, a_p, eta)
+        assert 0 < s * s < 1 - a_p
+    _, a_tl, a_pl = sampler.step_coefficients(sched, sched.num_steps)
+    assert a_pl == 1.0 and sampler.ddim_sigma(a_tl, a_pl, 1.0) == 0.0
+    # with the true eps the step lands on the stated marginal
+    x0, e_true = rng.standard_normal((3, 4)), rng.standard_normal((3, 4))
+    xt = math.sqrt(a_t) * x0 + math.sqrt(1 - a_t) * e_true
+    s = sampler.ddim_sigma(a_t, a_p, 0.7)
+    got = sampler.ddim_update_stochastic(xt, e_true, a_t, a_p, 0.7, z)
+    assert np.allclose(got, math.sqrt(a_p) * x0 + math.sqrt(1 - a_p - s * s) * e_true + s * z)
+
+
+def test_stochastic_step_uses_the_counter_noise_per_request():
+    from dataclasses import replace
+    sched = replace(synth.Schedule(num_steps=10), eta=0.5, seed=99)
+    rng = np.random.default_rng(1)
+    lat = rng.standard_normal((2, 2, 4, 4, 2))
+    net = lambda x, txt, t: 0.1 * x
+    got = sampler.denoise_step(None, None, lat, np.zeros((2, 1, 1)), None, sched, 4, eps_fn=net)
+    t, a_t, a_p = sampler.step_coefficients(sched, 4)
+    for r in range(2):
+        z = sampler.counter_normals(99, r, 4, lat[r].size).reshape(lat[r].shape)
+        assert np.allclose(got[r], sampler.ddim_update_stochastic(lat[r], 0.1 * lat[r], a_t, a_p, 0.5, z))
+    again = sampler.denoise_step(None, None, lat, np.zeros((2, 1, 1)), None, sched, 4, eps_fn=net)
+    assert np.array_equal(got, again)
+    other = sampler.denoise_step(None, None, lat, np.zeros((2, 1, 1)), None, replace(sched, seed=100), 4, eps_fn=net)
+    assert not np.allclose(got, other)
