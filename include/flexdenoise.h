@@ -75,12 +75,19 @@ typedef struct {
  * FC_SAMPLER_DDIM (eps-prediction): beta_i linear from beta_start to beta_end over
  * train_steps; the num_steps sampling timesteps are tau_j = j*(train_steps/num_steps),
  * visited in descending order; step s (1-based) maps t = tau_{N-s} to tau_{N-s-1}, the
- * last step to abar_prev = 1.  eta must be 0.
+ * last step to abar_prev = 1.  eta in 0..1: 0 is the deterministic update; eta > 0 adds
+ * sigma z with sigma = eta sqrt((1-abar_prev)/(1-abar_t)) sqrt(1 - abar_t/abar_prev) and
+ * keeps sqrt(1 - abar_prev - sigma^2) eps (the paper changes the denoising seed after a
+ * retrieval, which needs a sampler that draws noise).  z is a function of (seed,
+ * request index in the batch, step, element): Philox4x32-10 with counter (i/4 low word,
+ * i/4 high word, step, request) and key (seed low, seed high) gives elements 4(i/4) ..
+ * +3; an output word w becomes u = ((w >> 8) + 0.5) 2^-24; words (0, 1) and (2, 3) are
+ * Box-Muller pairs (sqrt(-2 ln u_a) cos(2 pi u_b), ... sin(2 pi u_b)).
  * FC_SAMPLER_FLOW_EULER (variant; the network output is the velocity noise - x0 of the
  * straight path x_sigma = (1 - sigma) x0 + sigma noise): sigma_j = j/N; step s goes from
  * sigma_{N-s+1} to sigma_{N-s}, x <- x + (sigma_{N-s} - sigma_{N-s+1}) v, the network is
  * evaluated at t = sigma_{N-s+1} * train_steps (train_steps % num_steps == 0 required);
- * beta_* and eta are not used.  The resume loop is the same for both. */
+ * beta_* are not used and eta must be 0.  The resume loop is the same for both. */
 #define FC_SAMPLER_DDIM 0
 #define FC_SAMPLER_FLOW_EULER 1
 typedef struct {
@@ -90,6 +97,7 @@ typedef struct {
   float guidance_scale; /* used only when null_cond != NULL */
   float eta;
   int32_t sampler;      /* FC_SAMPLER_* */
+  uint64_t seed;        /* key of the noise when eta > 0 */
 } fc_schedule;
 
 /* Create a model for `cfg` on the current device.  *out receives the handle.
@@ -136,8 +144,9 @@ int fc_workspace_bytes(const fc_model* m, int32_t batch_requests, int32_t use_cf
  *              NULL for no classifier-free guidance
  *   eps_out    dev, fp32, same shape as latent, receives the (guided) noise
  *              estimate; may be NULL
- * Errors: FC_ERR_NULL, FC_ERR_STATE, FC_ERR_RANGE (step not in 1..N, R < 1),
- * FC_ERR_UNSUPPORTED (eta != 0), FC_ERR_WORKSPACE, FC_ERR_DEVICE. */
+ * Errors: FC_ERR_NULL, FC_ERR_STATE, FC_ERR_RANGE (step not in 1..N, R < 1,
+ * eta outside 0..1), FC_ERR_UNSUPPORTED (eta != 0 with the Euler sampler),
+ * FC_ERR_WORKSPACE, FC_ERR_DEVICE. */
 int fc_denoise_step(fc_model* m, float* latent, const float* cond, const float* null_cond,
                     const fc_schedule* sched, int32_t step, int32_t batch_requests,
                     float* eps_out, void* workspace, size_t workspace_bytes, void* hip_stream);
@@ -167,6 +176,7 @@ int fc_denoise_resume_ex(fc_model* m, float* latent, const float* cond, const fl
 /* The four coefficients of a step, as the update kernel receives them (computed in
  * double, rounded to float), for x0 = (x - c1 e) / c0, x <- c2 x0 + c3 e:
  * DDIM: out4 = { sqrt(abar_t), sqrt(1-abar_t), sqrt(abar_prev), sqrt(1-abar_prev) };
+ * with eta > 0 the fourth is sqrt(1 - abar_prev - sigma^2);
  * Euler: { 1, 0, 1, sigma_next - sigma }.  *t_out = timestep the network is evaluated
  * at.  Host only. */
 int fc_schedule_coefficients(const fc_schedule* sched, int32_t step, float* out4, int32_t* t_out);

@@ -39,7 +39,7 @@ class fc_model_config(C.Structure):
 class fc_schedule(C.Structure):
     _fields_ = [("train_steps", C.c_int32), ("beta_start", C.c_float), ("beta_end", C.c_float),
                 ("num_steps", C.c_int32), ("guidance_scale", C.c_float), ("eta", C.c_float),
-                ("sampler", C.c_int32)]
+                ("sampler", C.c_int32), ("seed", C.c_uint64)]
 
 
 EXPORTS = {
@@ -132,7 +132,7 @@ def _cfg_struct(cfg: synth.ModelConfig) -> fc_model_config:
 
 
 def _sched_struct(s: synth.Schedule) -> fc_schedule:
-    return fc_schedule(s.train_steps, s.beta_start, s.beta_end, s.num_steps, s.guidance_scale, s.eta, s.sampler)
+    return fc_schedule(s.train_steps, s.beta_start, s.beta_end, s.num_steps, s.guidance_scale, s.eta, s.sampler, s.seed)
 
 
 # ------------------------------------------------------------------ the C calls, one to one

@@ -253,6 +253,9 @@ hipError_t launch_ln_modulate(int bf16, float* x, const void* y, const float* sh
                               hipStream_t s);
 hipError_t launch_cfg_ddim(float* x, const float* eps_c, const float* eps_u, float* eps_out, size_t n,
                            float gscale, float c0, float c1, float c2, float c3, hipStream_t s);
+hipError_t launch_cfg_ddim_noise(float* x, const float* eps_c, const float* eps_u, float* eps_out, size_t per_request,
+                                 int requests, float gscale, float c0, float c1, float c2, float c3, float sigma,
+                                 unsigned long long seed, int step, hipStream_t s);
 hipError_t launch_gemm(int bf16, int mode, const void* A, const void* Wt, int M, int N, int K,
                        const EpiParams& ep, hipStream_t s);
 hipError_t launch_attention(int bf16, const AttnParams& p, int impl, hipStream_t s);

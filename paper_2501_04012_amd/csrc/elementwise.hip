@@ -459,6 +459,66 @@ __global__ void k_cfg_ddim(float* __restrict__ x, const float* __restrict__ eps_
   }
 }
 
+// ---------------------------------------------------------------- guidance + stochastic DDIM update (eta > 0)
+// As above plus sigma * z, z standard normal, computed (not drawn) from (seed, request,
+// step, element) with Philox4x32-10 (Salmon et al., SC'11): element i of request r takes
+// lane i % 4 of the block with counter (i/4 low word, i/4 high word, step, r) and key
+// (seed low, seed high); a 32-bit output w becomes u = ((w >> 8) + 0.5) 2^-24; lanes
+// (0, 1) and (2, 3) are Box-Muller pairs.  One thread produces one block = 4 elements.
+__device__ __forceinline__ void philox4x32_10(unsigned (&c)[4], unsigned k0, unsigned k1) {
+#pragma unroll
+  for (int r = 0; r < 10; ++r) {
+    const unsigned long long p0 = 0xD2511F53ull * c[0], p1 = 0xCD9E8D57ull * c[2];
+    const unsigned n0 = (unsigned)(p1 >> 32) ^ c[1] ^ k0, n2 = (unsigned)(p0 >> 32) ^ c[3] ^ k1;
+    c[1] = (unsigned)p1; c[3] = (unsigned)p0; c[0] = n0; c[2] = n2;
+    k0 += 0x9E3779B9u; k1 += 0xBB67AE85u;
+  }
+}
+
+__global__ void k_cfg_ddim_noise(float* __restrict__ x, const float* __restrict__ eps_c,
+                                 const float* __restrict__ eps_u, float* __restrict__ eps_out, size_t per_request,
+                                 int requests, float gs, float c0, float c1, float c2, float c3, float sigma,
+                                 unsigned long long seed, int step) {
+  const size_t blocks_per_req = (per_request + 3) / 4;
+  const size_t b = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (b >= blocks_per_req * (size_t)requests) return;
+  const size_t r = b / blocks_per_req, blk = b % blocks_per_req;
+  unsigned c[4] = {(unsigned)blk, (unsigned)((unsigned long long)blk >> 32), (unsigned)step, (unsigned)r};
+  philox4x32_10(c, (unsigned)seed, (unsigned)(seed >> 32));
+  float z[4];
+#pragma unroll
+  for (int pr = 0; pr < 2; ++pr) {
+    const float ua = ((float)(c[2 * pr] >> 8) + 0.5f) * 5.9604644775390625e-8f;       // 2^-24: exact in fp32
+    const float ub = ((float)(c[2 * pr + 1] >> 8) + 0.5f) * 5.9604644775390625e-8f;
+    const float rad = sqrtf(-2.0f * logf(ua));
+    float sn, cs;
+    sincosf(6.283185307179586f * ub, &sn, &cs);
+    z[2 * pr] = rad * cs;
+    z[2 * pr + 1] = rad * sn;
+  }
+  const size_t base = r * per_request + blk * 4;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    if (blk * 4 + e >= per_request) break;
+    const size_t i = base + e;
+    float ev = eps_c[i];
+    if (eps_u) ev = eps_u[i] + gs * (ev - eps_u[i]);
+    const float x0 = (x[i] - c1 * ev) / c0;
+    x[i] = c2 * x0 + c3 * ev + sigma * z[e];
+    if (eps_out) eps_out[i] = ev;
+  }
+}
+
+hipError_t launch_cfg_ddim_noise(float* x, const float* eps_c, const float* eps_u, float* eps_out, size_t per_request,
+                                 int requests, float gscale, float c0, float c1, float c2, float c3, float sigma,
+                                 unsigned long long seed, int step, hipStream_t s) {
+  const size_t threads = (per_request + 3) / 4 * (size_t)requests;
+  if (threads == 0) return hipSuccess;
+  k_cfg_ddim_noise<<<(unsigned)((threads + 255) / 256), 256, 0, s>>>(x, eps_c, eps_u, eps_out, per_request, requests,
+                                                                      gscale, c0, c1, c2, c3, sigma, seed, step);
+  return hipGetLastError();
+}
+
 hipError_t launch_cfg_ddim(float* x, const float* eps_c, const float* eps_u, float* eps_out, size_t n,
                            float gscale, float c0, float c1, float c2, float c3, hipStream_t s) {
   if (n == 0) return hipSuccess;

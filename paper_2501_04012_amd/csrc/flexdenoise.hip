@@ -104,7 +104,9 @@ namespace {
 // ---------------------------------------------------------------- schedule (host, double)
 int schedule_check(const fc_schedule* s) {
   if (!s) return fail(FC_ERR_NULL, "schedule is NULL");
-  if (s->eta != 0.0f) return fail(FC_ERR_UNSUPPORTED, "only the deterministic sampler (eta = 0) is implemented");
+  if (!(s->eta >= 0.0f && s->eta <= 1.0f)) return fail(FC_ERR_RANGE, "eta must be in 0..1");
+  if (s->eta != 0.0f && s->sampler != FC_SAMPLER_DDIM)
+    return fail(FC_ERR_UNSUPPORTED, "eta belongs to the DDIM family; the Euler step draws no noise");
   if (s->train_steps < 1 || s->num_steps < 1 || s->num_steps > s->train_steps)
     return fail(FC_ERR_RANGE, "need 1 <= num_steps <= train_steps");
   if (s->sampler != FC_SAMPLER_DDIM && s->sampler != FC_SAMPLER_FLOW_EULER)
@@ -124,9 +126,11 @@ double abar_at(const fc_schedule* s, int t) {
   return prod;
 }
 
-int step_coefficients(const fc_schedule* s, int step, float* out4, int* t_out) {
+// out4: the update kernel's coefficients; *sigma_out: standard deviation of the noise the step adds (eta > 0)
+int step_coefficients(const fc_schedule* s, int step, float* out4, int* t_out, float* sigma_out = nullptr) {
   int rc = schedule_check(s);
   if (rc != FC_OK) return rc;
+  if (sigma_out) *sigma_out = 0.0f;
   const int N = s->num_steps;
   if (step < 1 || step > N) return fail(FC_ERR_RANGE, "step must be in 1..num_steps");
   const int stride = s->train_steps / N;
@@ -143,8 +147,13 @@ int step_coefficients(const fc_schedule* s, int step, float* out4, int* t_out) {
   const double a_p = step == N ? 1.0 : abar_at(s, (N - step - 1) * stride);
   out4[0] = (float)std::sqrt(a_t);
   out4[1] = (float)std::sqrt(1.0 - a_t);
+  // eta > 0: sigma = eta sqrt((1-abar_prev)/(1-abar_t)) sqrt(1 - abar_t/abar_prev); the eps
+  // direction keeps sqrt(1 - abar_prev - sigma^2)
+  const double sigma = s->eta == 0.0f ? 0.0
+                                      : (double)s->eta * std::sqrt((1.0 - a_p) / (1.0 - a_t)) * std::sqrt(1.0 - a_t / a_p);
   out4[2] = (float)std::sqrt(a_p);
-  out4[3] = (float)std::sqrt(1.0 - a_p);
+  out4[3] = (float)std::sqrt(std::max(1.0 - a_p - sigma * sigma, 0.0));
+  if (sigma_out) *sigma_out = (float)sigma;
   if (t_out) *t_out = t;
   return FC_OK;
 }
@@ -431,9 +440,9 @@ int run_step(const Ctx& c, float* latent, const fc_schedule* sched, int step, fl
   const fc_model_config& cf = m->cfg;
   const Workspace& w = c.w;
   const int D = cf.hidden;
-  float coef[4];
+  float coef[4], sigma = 0.0f;
   int t = 0;
-  int rc = step_coefficients(sched, step, coef, &t);
+  int rc = step_coefficients(sched, step, coef, &t, &sigma);
   if (rc != FC_OK) return rc;
 
   // conditioning: sinusoid -> Linear -> SiLU -> Linear -> c; every adaLN layer reads SiLU(c)
@@ -489,8 +498,13 @@ int run_step(const Ctx& c, float* latent, const fc_schedule* sched, int step, fl
 
   const size_t n = (size_t)c.R * cf.frames * cf.height * cf.width * cf.channels;
   ProfScope ps(c, PC_CFG_DDIM);
-  HIP_TRY(launch_cfg_ddim(latent, w.eps, c.use_cfg ? w.eps + n : nullptr, eps_out, n, sched->guidance_scale,
-                          coef[0], coef[1], coef[2], coef[3], c.s));
+  if (sigma > 0.0f)
+    HIP_TRY(launch_cfg_ddim_noise(latent, w.eps, c.use_cfg ? w.eps + n : nullptr, eps_out, n / c.R, c.R,
+                                  sched->guidance_scale, coef[0], coef[1], coef[2], coef[3], sigma, sched->seed, step,
+                                  c.s));
+  else
+    HIP_TRY(launch_cfg_ddim(latent, w.eps, c.use_cfg ? w.eps + n : nullptr, eps_out, n, sched->guidance_scale,
+                            coef[0], coef[1], coef[2], coef[3], c.s));
   return FC_OK;
 }
 

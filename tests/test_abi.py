@@ -68,9 +68,18 @@ def test_schedule_errors_are_status_codes(fc):
         with pytest.raises(fc.FlexDenoiseError) as e:
             fc.fc_schedule_coefficients(sched, bad)
         assert e.value.status == -3
+    for bad_eta in (-0.1, 1.5):
+        with pytest.raises(fc.FlexDenoiseError) as e:
+            fc.fc_schedule_coefficients(replace(sched, eta=bad_eta), 1)
+        assert e.value.status == -3
     with pytest.raises(fc.FlexDenoiseError) as e:
-        fc.fc_schedule_coefficients(replace(sched, eta=0.5), 1)
+        fc.fc_schedule_coefficients(replace(sched, eta=0.5, sampler=synth.SAMPLER_FLOW_EULER), 1)
     assert e.value.status == -6
+    # eta > 0 keeps sqrt(1 - abar_prev - sigma^2) on the eps direction
+    coef, _ = fc.fc_schedule_coefficients(replace(sched, eta=0.5), 20)
+    _, a_t, a_p = sampler.step_coefficients(sched, 20)
+    sg = sampler.ddim_sigma(a_t, a_p, 0.5)
+    np.testing.assert_allclose(coef[3], math.sqrt(1 - a_p - sg * sg), rtol=2e-6)
 
 
 def test_weight_spec_matches_library_count_formula():

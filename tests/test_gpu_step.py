@@ -231,6 +231,48 @@ def test_flow_euler_variant_step_and_resume(fc):
         den.close()
 
 
+def test_stochastic_ddim_with_counter_noise(fc):
+    """eta > 0: the noise is a function of (seed, request, step, element), so the GPU step
+    must reproduce the oracle's step to fp32 accuracy, per request, for the tiny
+    configuration with two requests and guidance; another seed gives another latent; the
+    last step draws nothing; a free-running resume stays on the oracle's trajectory."""
+    import torch
+    w = synth.WORKLOADS["cfg5b"]
+    cfg = w.model
+    W = synth.make_weights(cfg, w.weight_seed)
+    lat, cond, null = synth.workload_inputs(w)
+    sched = replace(w.schedule, eta=0.6, seed=(7 << 32) + 12345)
+    den = fc.Denoiser(cfg, W, w.requests, True)
+    try:
+        d_cond, d_null = dev(cond), dev(null)
+        for step in (1, 26, 49):
+            d_lat = dev(lat)
+            den.step(d_lat, d_cond, d_null, sched, step)
+            torch.cuda.synchronize()
+            want = sampler.denoise_step(cfg, W, lat, cond, null, sched, step)
+            got = host(d_lat)
+            record(step=float(step), latent_rel_l2=rel_l2(got, want), latent_max_abs=max_abs(got, want))
+            assert rel_l2(got, want) <= F32_REL
+            # the noise matters at this eta: the deterministic step is somewhere else
+            assert rel_l2(sampler.denoise_step(cfg, W, lat, cond, null, replace(sched, eta=0.0), step), want) > 1e-3
+        a, b = dev(lat), dev(lat)
+        den.step(a, d_cond, d_null, sched, 26)
+        den.step(b, d_cond, d_null, replace(sched, seed=sched.seed + 1), 26)
+        c, d = dev(lat), dev(lat)
+        den.step(c, d_cond, d_null, sched, 50)                     # abar_prev = 1: sigma = 0
+        den.step(d, d_cond, d_null, replace(sched, eta=0.0), 50)
+        torch.cuda.synchronize()
+        assert not torch.equal(a, b) and torch.equal(c, d)
+        x = dev(lat)
+        den.resume(x, d_cond, d_null, sched, 40)
+        torch.cuda.synchronize()
+        want = sampler.denoise_resume(cfg, W, lat, cond, null, sched, 40)
+        record(final_latent_rel_l2=rel_l2(host(x), want))
+        assert rel_l2(host(x), want) <= 1e-3
+    finally:
+        den.close()
+
+
 def test_api_errors(fc):
     import torch
     w = synth.WORKLOADS["cfg1"]
@@ -267,7 +309,11 @@ def test_api_errors(fc):
             fc.fc_denoise_step(m, None, d_cond, None, w.schedule, 25, 1, None, ws)
         assert e.value.status == -1
         with pytest.raises(fc.FlexDenoiseError) as e:
-            fc.fc_denoise_step(m, d_lat, d_cond, None, replace(w.schedule, eta=1.0), 25, 1, None, ws)
+            fc.fc_denoise_step(m, d_lat, d_cond, None, replace(w.schedule, eta=1.5), 25, 1, None, ws)
+        assert e.value.status == -3
+        with pytest.raises(fc.FlexDenoiseError) as e:
+            fc.fc_denoise_step(m, d_lat, d_cond, None,
+                               replace(w.schedule, eta=0.5, sampler=synth.SAMPLER_FLOW_EULER), 25, 1, None, ws)
         assert e.value.status == -6
         torch.cuda.synchronize()
         assert np.array_equal(host(d_lat), lat)               # no failed call touched the latent
