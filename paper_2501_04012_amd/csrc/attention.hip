@@ -207,46 +207,50 @@ static hipError_t run_short_strided(const AttnParams& p, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------- short strided sequences on the matrix cores
-// Same problem as above for bf16 and T <= 16: the scalar kernel spends its time in
-// bf16->fp32 unpacking and 2 T HD FMAs per query; here one wave does a sequence with
-// 3 + HD/16 small MFMAs and the kernel is bound by reading q, k, v and writing o once.
+// Same problem as above for bf16 and T <= 64: the scalar kernel spends its time in
+// bf16->fp32 unpacking and 2 T HD FMAs per query; here the work is a handful of small
+// MFMAs per 16 queries and the kernel is bound by reading q, k, v and writing o once.
+// The sequence is cut into KB = ceil(T / 16) blocks of 16 tokens (KB = 1, 2 or 4).
 //   S^T (16 keys x 16 queries) = K (A operand) x Q^T (B operand), v_mfma_f32_16x16x32_bf16,
-//   contraction over the head dim in steps of 32.  Operand lane l = (i, h), i = l % 16,
-//   h = l / 16: row/column i, k = 8h .. 8h+7.  D: column i, rows 4h + e in register e.
-//   So lane (i, h) holds the scores of query i against keys 4h .. 4h+3: after exp2 and
-//   rounding they are, as they stand, the B operand (k = 4h .. 4h+3) of
-//   O^T (16 dims x 16 queries) += V^T (A operand) x P^T, v_mfma_f32_16x16x16_bf16, whose
-//   A fragments (dim i, keys 4h .. 4h+3) are transpose reads of the row-major V tile.
-// A workgroup of 4 waves stages SM_SB neighbouring sequences ([SB][16][PITCH] per tensor,
-// coalesced: for one t the SB rows are contiguous in memory); each wave then takes
-// SM_SB / 4 of them.  PITCH/8 is odd so that the 16 rows of a fragment read fall into
-// distinct bank groups.
+//   contraction over the head dim in steps of 32, one such tile per key block.  Operand
+//   lane l = (i, h), i = l % 16, h = l / 16: row/column i, k = 8h .. 8h+7.  D: column i,
+//   rows 4h + e in register e.  So lane (i, h) holds the scores of query i against keys
+//   16 kb + 4h .. + 3: after exp2 and rounding they are, as they stand, the B operand
+//   (k = 4h .. 4h+3) of O^T (16 dims x 16 queries) += V^T (A operand) x P^T,
+//   v_mfma_f32_16x16x16_bf16, whose A fragments (dim i, keys 4h .. 4h+3) are transpose
+//   reads of the row-major V tile.  All keys of a query are seen at once: plain two-pass
+//   softmax in registers, no running maximum.
+// A workgroup of 4 waves stages SB = 8 / KB neighbouring sequences ([SB][16 KB][PITCH] per
+// tensor, coalesced: for one t the SB rows are contiguous in memory) and has 8 work items
+// (sequence, query block), two per wave.  PITCH/8 is odd so that the 16 rows of a
+// fragment read fall into distinct bank groups.
 typedef __attribute__((ext_vector_type(4))) short i16x4;
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
-constexpr int SM_SB = 8;
-template <int HD>
+template <int HD, int KB>
 struct ShortMfmaCfg {
+  static constexpr int SB = 8 / KB;                                      // sequences per workgroup
+  static constexpr int TP = 16 * KB;                                     // padded sequence length
   static constexpr int PITCH = ((HD / 8) % 2 == 1) ? HD : HD + 8;      // elements
-  static constexpr int TILE = SM_SB * 16 * PITCH;                        // elements per tensor
+  static constexpr int TILE = SB * TP * PITCH;                           // elements per tensor
   static constexpr size_t SMEM = (size_t)3 * TILE * sizeof(bf16_t) + 64; // slack: the last V fragment reads past HD
   static constexpr int KSTEPS = (HD + 31) / 32;
   static constexpr int DT = (HD + 15) / 16;
 };
 
-template <int HD>
+template <int HD, int KB>
 __global__ __launch_bounds__(256) void k_attn_short_mfma(AttnParams p) {
-  using C = ShortMfmaCfg<HD>;
+  using C = ShortMfmaCfg<HD, KB>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_sm[];
   bf16_t* qs = (bf16_t*)smem_sm;
   bf16_t* ks = qs + C::TILE;
   bf16_t* vs = ks + C::TILE;
-  const int Tn = p.nq;                       // == nk, <= 16
-  const int sblocks = (p.groups + SM_SB - 1) / SM_SB;
+  const int Tn = p.nq;                       // == nk, <= 16 KB
+  const int sblocks = (p.groups + C::SB - 1) / C::SB;
   int bid = blockIdx.x;
   const int sb = bid % sblocks; bid /= sblocks;
   const int head = bid % p.heads;
   const int b = bid / p.heads;
-  const int s0 = sb * SM_SB;
+  const int s0 = sb * C::SB;
   const size_t bh = ((size_t)b * p.heads + head) * (size_t)p.q_tokens;
   const bf16_t* qg = (const bf16_t*)p.q + bh * HD;
   const bf16_t* kg = (const bf16_t*)p.k + bh * HD;
@@ -254,10 +258,10 @@ __global__ __launch_bounds__(256) void k_attn_short_mfma(AttnParams p) {
 
   // ---- stage: rows t >= Tn are zero (V rows of masked keys must not hold NaN patterns)
   constexpr int CPR = HD / 8;
-  for (int ch = threadIdx.x; ch < 16 * SM_SB * CPR; ch += 256) {
+  for (int ch = threadIdx.x; ch < C::TP * C::SB * CPR; ch += 256) {
     const int c = ch % CPR, r = ch / CPR;
-    const int sq = r % SM_SB, t = r / SM_SB;
-    const int loff = (sq * 16 + t) * C::PITCH + c * 8;
+    const int sq = r % C::SB, t = r / C::SB;
+    const int loff = (sq * C::TP + t) * C::PITCH + c * 8;
     f32x4 zq = {0.0f, 0.0f, 0.0f, 0.0f}, zk = zq, zv = zq;
     if (t < Tn) {
       int sg = s0 + sq; sg = sg < p.groups ? sg : p.groups - 1;   // sequences past the last are never stored
@@ -276,56 +280,73 @@ __global__ __launch_bounds__(256) void k_attn_short_mfma(AttnParams p) {
   const int li = lane & 15, lh = lane >> 4;
   const int tr_r = li >> 2, tr_a = li & 3;
 #pragma unroll
-  for (int w = 0; w < SM_SB / 4; ++w) {
-    const int sq = wave * (SM_SB / 4) + w;
-    if (s0 + sq >= p.groups) break;                      // wave-uniform
-    const bf16_t* qrow = qs + (sq * 16 + li) * C::PITCH;
-    const bf16_t* krow = ks + (sq * 16 + li) * C::PITCH;
-    f32x4 sacc = {0.0f, 0.0f, 0.0f, 0.0f};
+  for (int w = 0; w < 2; ++w) {
+    const int item = wave + 4 * w;                       // (sequence, query block)
+    const int sq = item / KB, qb = item % KB;
+    if (s0 + sq >= p.groups || 16 * qb >= Tn) continue;  // wave-uniform
+    const bf16_t* qrow = qs + (sq * C::TP + 16 * qb + li) * C::PITCH;
+    f32x4 sacc[KB];
+#pragma unroll
+    for (int kb = 0; kb < KB; ++kb) sacc[kb] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int st = 0; st < C::KSTEPS; ++st) {
       const int d0 = 32 * st + 8 * lh;
-      bf16x8 qf, kf;
+      const bool in = d0 < HD;                           // HD % 8 == 0: a fragment is all in or all out
+      bf16x8 qf;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) { qf[e] = (bf16_t)0.0f; kf[e] = (bf16_t)0.0f; }
-      if (d0 < HD) {                                     // HD % 8 == 0: a fragment is all in or all out
-        qf = *(const bf16x8*)(qrow + d0);
-        kf = *(const bf16x8*)(krow + d0);
+      for (int e = 0; e < 8; ++e) qf[e] = (bf16_t)0.0f;
+      if (in) qf = *(const bf16x8*)(qrow + d0);
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) {
+        bf16x8 kf;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) kf[e] = (bf16_t)0.0f;
+        if (in) kf = *(const bf16x8*)(ks + (sq * C::TP + 16 * kb + li) * C::PITCH + d0);
+        sacc[kb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf, sacc[kb], 0, 0, 0);
       }
-      sacc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf, sacc, 0, 0, 0);
     }
-    // ---- softmax over the 16 keys of query li: 4 here, the rest in lanes li + 16 h'
-    float sc[4];
+    // ---- softmax over the keys of query 16 qb + li: 4 KB of them here, the rest in lanes li + 16 h'
+    float sc[KB][4];
     float mx = -INFINITY;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      sc[e] = (4 * lh + e < Tn) ? sacc[e] * p.scale_log2 : -INFINITY;
-      mx = fmaxf(mx, sc[e]);
-    }
+    for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        sc[kb][e] = (16 * kb + 4 * lh + e < Tn) ? sacc[kb][e] * p.scale_log2 : -INFINITY;
+        mx = fmaxf(mx, sc[kb][e]);
+      }
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));              // finite: key 0 is valid
-    bf16x4 pb;
+    i16x4 pf[KB];
     float sum = 0.0f;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      pb[e] = (bf16_t)__builtin_amdgcn_exp2f(sc[e] - mx);
-      sum += (float)pb[e];
+    for (int kb = 0; kb < KB; ++kb) {
+      bf16x4 pb;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        pb[e] = (bf16_t)__builtin_amdgcn_exp2f(sc[kb][e] - mx);
+        sum += (float)pb[e];
+      }
+      pf[kb] = __builtin_bit_cast(i16x4, pb);
     }
     sum += __shfl_xor(sum, 16, 64);
     sum += __shfl_xor(sum, 32, 64);
     const float inv = 1.0f / sum;
-    const i16x4 pf = __builtin_bit_cast(i16x4, pb);
 
-    const int tok = li * p.q_istride + s0 + sq;
+    const int tq = 16 * qb + li;
+    const int tok = tq * p.q_istride + s0 + sq;
     bf16_t* orow = (bf16_t*)p.out + ((size_t)b * p.q_tokens + tok) * ((size_t)p.heads * HD) + (size_t)head * HD;
-    const bf16_t* vtile = vs + (sq * 16 + 4 * lh + tr_r) * C::PITCH + 4 * tr_a;
+    const bf16_t* vtile = vs + (sq * C::TP + 4 * lh + tr_r) * C::PITCH + 4 * tr_a;
 #pragma unroll
     for (int c = 0; c < C::DT; ++c) {
-      const bf16x4 vf = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(vtile + 16 * c));
-      f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
-      const f32x4 o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(i16x4, vf), pf, zero, 0, 0, 0);
+      f32x4 o = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+      for (int kb = 0; kb < KB; ++kb) {
+        const bf16x4 vf = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(vtile + 16 * kb * C::PITCH + 16 * c));
+        o = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(i16x4, vf), pf[kb], o, 0, 0, 0);
+      }
       const int dd = 16 * c + 4 * lh;
-      if (li < Tn && dd < HD) {
+      if (tq < Tn && dd < HD) {
         bf16x4 ov;
 #pragma unroll
         for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)(o[e] * inv);
@@ -336,17 +357,17 @@ __global__ __launch_bounds__(256) void k_attn_short_mfma(AttnParams p) {
 }
 
 static bool short_mfma_ok(const AttnParams& p) {
-  return (p.hd == 64 || p.hd == 72) && p.nq == p.nk && p.nq >= 1 && p.nq <= 16 && p.q_gstride == 1 &&
+  return (p.hd == 64 || p.hd == 72) && p.nq == p.nk && p.nq >= 1 && p.nq <= 64 && p.q_gstride == 1 &&
          p.k_gstride == 1 && p.q_istride == p.k_istride && p.q_istride == p.groups && p.q_tokens == p.k_tokens &&
          !p.kv_shared_tail;
 }
 
-template <int HD>
-static hipError_t run_short_mfma(const AttnParams& p, hipStream_t s) {
-  using C = ShortMfmaCfg<HD>;
-  const long long blocks = (long long)p.B * p.heads * ((p.groups + SM_SB - 1) / SM_SB);
+template <int HD, int KB>
+static hipError_t run_short_mfma_kb(const AttnParams& p, hipStream_t s) {
+  using C = ShortMfmaCfg<HD, KB>;
+  const long long blocks = (long long)p.B * p.heads * ((p.groups + C::SB - 1) / C::SB);
   if (blocks == 0) return hipSuccess;
-  auto kern = k_attn_short_mfma<HD>;
+  auto kern = k_attn_short_mfma<HD, KB>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::SMEM);
@@ -355,6 +376,13 @@ static hipError_t run_short_mfma(const AttnParams& p, hipStream_t s) {
   }
   kern<<<(unsigned)blocks, 256, C::SMEM, s>>>(p);
   return hipGetLastError();
+}
+
+template <int HD>
+static hipError_t run_short_mfma(const AttnParams& p, hipStream_t s) {
+  if (p.nq <= 16) return run_short_mfma_kb<HD, 1>(p, s);
+  if (p.nq <= 32) return run_short_mfma_kb<HD, 2>(p, s);
+  return run_short_mfma_kb<HD, 4>(p, s);
 }
 
 template <typename T, int HD>

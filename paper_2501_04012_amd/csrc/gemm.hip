@@ -228,6 +228,65 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
   }
 }
 
+// ---------------------------------------------------------------- bf16 MFMA kernel for products with few tiles
+// A 128x128 grid of C leaves most CUs idle when there are only a few tiles, and each of
+// them walks the whole K alone.  Here a workgroup owns one 32x32 tile and
+// its 4 waves split K; fragments come straight from global memory (each lane its own
+// 16 bytes: row i of A or Wt, k = 8h .. 8h+7 of the wave's current 16-wide step), the four
+// partial tiles are added through LDS in a fixed order, and wave 0 runs the column-form
+// epilogue.  Needs K % 64 == 0 and 16-byte aligned rows, like the big kernel.
+template <typename Epi>
+__global__ __launch_bounds__(256) void k_gemm_skinny(const bf16_t* __restrict__ A, const bf16_t* __restrict__ Wt, int M,
+                                                     int N, int K, Epi epi) {
+  __shared__ float part[3][64][16 + 1];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int li = lane & 31, lh = lane >> 5;
+  const int m0 = blockIdx.y * 32, n0 = blockIdx.x * 32;
+  const int am = m0 + li < M ? m0 + li : M - 1;          // rows past the edge: computed from a valid row, never stored
+  const int bn = n0 + li < N ? n0 + li : N - 1;
+  const int kq = K / 4;
+  const bf16_t* ap = A + (size_t)am * K + wave * kq + lh * 8;
+  const bf16_t* bp = Wt + (size_t)bn * K + wave * kq + lh * 8;
+  f32x16 acc;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+  for (int k = 0; k < kq; k += 64) {                     // kq % 16 == 0; 4 steps per trip, loads first
+    bf16x8 fa[4], fb[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (k + 16 * u < kq) { fa[u] = *(const bf16x8*)(ap + k + 16 * u); fb[u] = *(const bf16x8*)(bp + k + 16 * u); }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (k + 16 * u < kq) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[u], fb[u], acc, 0, 0, 0);
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) part[wave - 1][lane][r] = acc[r];
+  }
+  __syncthreads();
+  if (wave > 0) return;
+#pragma unroll
+  for (int w = 0; w < 3; ++w)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] += part[w][lane][r];
+  // D: lane (li, lh) holds column li, rows 8 g + 4 lh + e in register 4 g + e
+  const auto col = epi.col(n0 + li);
+#pragma unroll
+  for (int g = 0; g < 4; ++g) {
+    float v[4] = {acc[4 * g], acc[4 * g + 1], acc[4 * g + 2], acc[4 * g + 3]};
+    epi.store4(col, m0 + g * 8 + lh * 4, v);
+  }
+}
+
+template <int MODE>
+static hipError_t run_skinny(const void* A, const void* Wt, int M, int N, int K, const EpiParams& ep, hipStream_t s) {
+  using Epi = Epilogue<bf16_t, MODE>;
+  Epi epi = Epi::make(ep, M, N);
+  dim3 grid(ceil_div(N, 32), ceil_div(M, 32));
+  k_gemm_skinny<Epi><<<grid, 256, 0, s>>>((const bf16_t*)A, (const bf16_t*)Wt, M, N, K, epi);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------- plain kernel (any T, any shape)
 // 64x64 block tile, BK = 16, 256 threads each owning a 4(row) x 4(col) micro-tile.
 template <typename T, typename Epi>
@@ -302,6 +361,13 @@ static hipError_t dispatch_mode(int bf16, const void* A, const void* Wt, int M, 
                                 hipStream_t s) {
   if (!bf16) return run_plain<float, MODE>(A, Wt, M, N, K, ep, s);
   bool aligned = (((uintptr_t)A | (uintptr_t)Wt) & 15) == 0;
+  // very few tiles (a request's text rows), or an N too narrow for the tile kernel (a 16-wide
+  // output head): split K inside a workgroup instead.  Measured against the 128x128
+  // configuration it wins below about 32 of its tiles and loses above (its fragment loads
+  // are 32-byte pieces of rows).
+  if (aligned && K % 64 == 0 && ((long long)ceil_div(M, 128) * ceil_div(N, 128) < 32 || N < 32) &&
+      ceil_div(M, 32) <= 65535)
+    return run_skinny<MODE>(A, Wt, M, N, K, ep, s);
   if (MODE != EPI_UNPATCH) {
     // the MFMA kernel writes 16-byte runs of a row and reads bias / gate four at a time
     aligned = aligned && N % 8 == 0 && (((uintptr_t)ep.bias | (uintptr_t)ep.gate) & 15) == 0;

@@ -125,6 +125,10 @@ WORKLOADS: Dict[str, Workload] = {
                       text_seed=520, null_seed=503, requests=4, resume_k=(10, 20)),
     "cfg5b": Workload("cfg5b", replace(_TINY, depth=28), weight_seed=310, latent_seed=501,
                       text_seed=520, null_seed=503, requests=4, resume_k=(10, 20)),
+    # a sixth, additional workload with the latent shape the paper states for its model
+    # (64 frames x 40 x 64 x 4, Sec. 2.3): 40 960 tokens, spatial sequences of 640, temporal of 64
+    "cfg6": Workload("cfg6", replace(_FACT, frames=64, height=40, width=64), weight_seed=600, latent_seed=601,
+                     text_seed=602, null_seed=None),
 }
 
 

@@ -21,7 +21,9 @@ def _torch():
 # --------------------------------------------------------------------------- linear layers
 
 LIN_SHAPES = [
-    (1, 32, 64), (300, 200, 128), (513, 384, 256), (64, 1152, 1152), (127, 96, 64),
+    (1, 32, 64), (300, 200, 128), (513, 384, 256), (64, 1152, 1152), (127, 96, 64),   # few tiles: split-K kernel
+    (2100, 1024, 128),       # the 128x128 configuration, ragged M
+    (2500, 48, 192),         # narrow N, many rows (the output head's shape class), ragged both ways
     (8209, 2048, 128),       # enough tiles for the 256x256 configuration, ragged M
     (8200, 1152, 128),       # N a multiple of 192 that 256 would pad: the 256x192 configuration, ragged M
     (250, 160, 72),          # K not a multiple of 64: plain kernel

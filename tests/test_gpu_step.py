@@ -57,6 +57,21 @@ def test_small_ragged_model_with_sharp_softmax(fc, mode, dtype):
     check(*got, *want, bf16=dtype == synth.DT_BF16)
 
 
+@pytest.mark.parametrize("frames", [16, 17, 32, 37, 64])
+def test_small_factorized_model_frame_counts(fc, frames):
+    """Temporal attention over up to 64 frames (one, two or four 16-token blocks per
+    sequence in the matrix-core kernel, ragged last block), bf16, guidance, two requests."""
+    cfg = synth.ModelConfig(frames=frames, height=8, width=12, channels=4, patch=2, hidden=256, heads=4, mlp_dim=512,
+                            depth=1, text_len=26, text_dim=96, attn_mode=synth.ATTN_FACTORIZED_CROSS,
+                            dtype=synth.DT_BF16)
+    w = synth.Workload("frames", cfg, weight_seed=27, latent_seed=28, text_seed=29, null_seed=30, requests=2)
+    W = synth.make_weights(cfg, 27, std=0.08)
+    inputs = synth.workload_inputs(w)
+    got = run_step_gpu(fc, w, weights=W, inputs=inputs)
+    want = oracle_step(w, cfg, W, inputs, w.step)
+    check(*got, *want, bf16=True)
+
+
 @pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
 def test_small_model_with_16_latent_channels(fc, dtype):
     """2x2 patches of 16 channels (patch features K = 64, the shape of the full-3D
@@ -77,6 +92,18 @@ def test_cfg2_bf16_factorized_block(fc):
     inputs = synth.workload_inputs(w)
     got = run_step_gpu(fc, w, weights=W, inputs=inputs)
     want = oracle_step(w, w.model, W, inputs, w.step)
+    check(*got, *want, bf16=True)
+
+
+def test_cfg6_paper_shaped_latent_factorized_block(fc):
+    """The latent shape the paper states for its model (64 x 40 x 64 x 4: 40 960 tokens,
+    spatial sequences of 640 tokens, temporal ones of 64), one factorized bf16 block,
+    against the fp32 oracle."""
+    w = synth.WORKLOADS["cfg6"]
+    W = synth.make_weights(w.model, w.weight_seed)
+    inputs = synth.workload_inputs(w)
+    got = run_step_gpu(fc, w, weights=W, inputs=inputs)
+    want = oracle_step(w, w.model, W, inputs, w.step, dtype=np.float32)
     check(*got, *want, bf16=True)
 
 
