@@ -46,6 +46,7 @@ template <int BM, int BN, int BK, int WR, int WC, int S, typename Epi>
 __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __restrict__ A,
                                                             const bf16_t* __restrict__ Wt, int M, int N, int K,
                                                             int tiles_m, int tiles_n, Epi epi) {
+  static_assert(S == 2, "two stages: one being multiplied, one in flight");
   constexpr int NW = WR * WC;
   constexpr int WTM = BM / WR, WTN = BN / WC;
   constexpr int TM = WTM / 32, TN = WTN / 32;
@@ -65,37 +66,48 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
   const int wr = wave / WC, wc = wave % WC;
   const int li = lane & 31, lh = lane >> 5;
 
+  // ---- tiles of this workgroup: virtual ids blockIdx.x, + gridDim.x, ... below `padded`
+  // (the grid may be one workgroup per slot of the chip: persistent).  gridDim.x is a
+  // multiple of 8, so every id of a workgroup lands on its XCD.
   const int total = tiles_m * tiles_n;
-  const int bid = blockIdx.x;
-  const int xcd = bid & 7, local = bid >> 3;
-  const int t = ((local >> 5) * 8 + xcd) * 32 + (local & 31);
-  if (t >= total) return;
-  constexpr int GM = 8;
-  const int per_group = GM * tiles_n;
-  const int group = t / per_group;
-  const int first_m = group * GM;
-  const int gsz = min(tiles_m - first_m, GM);
-  const int tm = first_m + (t % per_group) % gsz;
-  const int tn = (t % per_group) / gsz;
-  const int bm0 = tm * BM, bn0 = tn * BN;
+  const int padded = (total + 255) / 256 * 256;
+  auto tile_of = [&](int vb, int& bm0, int& bn0) {
+    const int xcd = vb & 7, local = vb >> 3;
+    const int t = ((local >> 5) * 8 + xcd) * 32 + (local & 31);
+    if (t >= total) return false;
+    constexpr int GM = 8;
+    const int per_group = GM * tiles_n;
+    const int group = t / per_group;
+    const int first_m = group * GM;
+    const int gsz = min(tiles_m - first_m, GM);
+    bm0 = (first_m + (t % per_group) % gsz) * BM;
+    bn0 = ((t % per_group) / gsz) * BN;
+    return true;
+  };
+  auto next_tile = [&](int& vb, int& bm0, int& bn0) {       // advances vb to this workgroup's next real tile
+    for (vb += gridDim.x; vb < padded; vb += gridDim.x)
+      if (tile_of(vb, bm0, bn0)) return true;
+    return false;
+  };
 
-  // ---- global source pointers of this lane for its LPW wave-loads
-  const bf16_t* gp[LPW];
+  // ---- global source pointers of this lane for its LPW wave-loads of a tile
+  auto sources = [&](int bm0, int bn0, const bf16_t* (&gp)[LPW]) {
 #pragma unroll
-  for (int j = 0; j < LPW; ++j) {
-    const int wl = wave + NW * j;
-    const int line_in = lane >> 4, slot = lane & 15;
-    const int row = wl * RW + line_in * RPL + slot / CPR;
-    const int kc = (slot % CPR) ^ ((wl * 4 + line_in) % CPR);
-    if (row < BM) {
-      int gm = bm0 + row; gm = gm < M ? gm : M - 1;
-      gp[j] = A + (size_t)gm * K + kc * 8;
-    } else {
-      int gn = bn0 + row - BM; gn = gn < N ? gn : N - 1;
-      gp[j] = Wt + (size_t)gn * K + kc * 8;
+    for (int j = 0; j < LPW; ++j) {
+      const int wl = wave + NW * j;
+      const int line_in = lane >> 4, slot = lane & 15;
+      const int row = wl * RW + line_in * RPL + slot / CPR;
+      const int kc = (slot % CPR) ^ ((wl * 4 + line_in) % CPR);
+      if (row < BM) {
+        int gm = bm0 + row; gm = gm < M ? gm : M - 1;
+        gp[j] = A + (size_t)gm * K + kc * 8;
+      } else {
+        int gn = bn0 + row - BM; gn = gn < N ? gn : N - 1;
+        gp[j] = Wt + (size_t)gn * K + kc * 8;
+      }
     }
-  }
-  auto issue = [&](int kt, int stage) {
+  };
+  auto issue = [&](const bf16_t* const (&gp)[LPW], int kt, int stage) {
 #pragma unroll
     for (int j = 0; j < LPW; ++j) {
       const int wl = wave + NW * j;
@@ -110,121 +122,148 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
   const int b_row = (rb / RPL) * 256 + (rb % RPL) * CPR * 16, b_x = (rb / RPL) % CPR;
   constexpr int TILE_STRIDE = (32 / RPL) * 256;   // 32 rows further down
 
-  f32x16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
+  int vb = (int)blockIdx.x - (int)gridDim.x, bm0 = 0, bn0 = 0;
+  if (!next_tile(vb, bm0, bn0)) return;
+  const bf16_t* gp[LPW];
+  sources(bm0, bn0, gp);
   const int nkt = K / BK;
-#pragma unroll
-  for (int p = 0; p < S - 1; ++p)
-    if (p < nkt) issue(p, p);
+  issue(gp, 0, 0);
+  wait_vm<0>();
+  __builtin_amdgcn_s_barrier();
+  int g = 0;                                       // K tiles consumed so far; the current one sits in stage g & 1
 
-  for (int kt = 0; kt < nkt; ++kt) {
-    if (kt + S - 2 < nkt) wait_vm<LPW * (S - 2)>(); else wait_vm<0>();
-    __builtin_amdgcn_s_barrier();
-    if (kt + S - 1 < nkt) issue(kt + S - 1, (kt + S - 1) % S);
-    const unsigned char* st = smem + (kt % S) * STAGE_BYTES;
-    // Fragment reads run one 16-wide k-slice ahead of the MFMAs that consume them, in
-    // two register sets.  The scheduling groups below pin the instruction order the
-    // compiler would otherwise collapse into read-all / wait / multiply: after the first
-    // slice's reads, every read of slice ks+1 is paired with one MFMA of slice ks, so the
-    // LDS latency is spent under matrix work of the same wave.
-    constexpr int KS = BK / 16;
-    bf16x8 fa[2][TM], fb[2][TN];
-    auto load = [&](int ks, bf16x8 (&xa)[TM], bf16x8 (&xb)[TN]) {
-      const unsigned char* pa = st + a_row + (((2 * ks + lh) ^ a_x) << 4);
-      const unsigned char* pb = st + b_row + (((2 * ks + lh) ^ b_x) << 4);
-#pragma unroll
-      for (int i = 0; i < TM; ++i) xa[i] = *(const bf16x8*)(pa + i * TILE_STRIDE);
-#pragma unroll
-      for (int j = 0; j < TN; ++j) xb[j] = *(const bf16x8*)(pb + j * TILE_STRIDE);
-    };
-    load(0, fa[0], fb[0]);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      if (ks + 1 < KS) load(ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          // row-run epilogues want a lane to hold consecutive n: D rows come from the A
-          // operand, so the weight fragment goes there (the operand layouts are alike)
-          acc[i][j] = Epi::kRowRuns
-                          ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks & 1][j], fa[ks & 1][i], acc[i][j], 0, 0, 0)
-                          : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
-    }
-    constexpr int kDsRead = 0x100, kMfma = 0x008;
-    __builtin_amdgcn_sched_group_barrier(kDsRead, TM + TN, 0);
-#pragma unroll
-    for (int ks = 0; ks + 1 < KS; ++ks) {
-#pragma unroll
-      for (int r = 0; r < TM + TN; ++r) {
-        __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);
-      }
-      if (TM * TN > TM + TN) __builtin_amdgcn_sched_group_barrier(kMfma, TM * TN - (TM + TN), 0);
-    }
-    __builtin_amdgcn_sched_group_barrier(kMfma, TM * TN, 0);
-  }
+  // One pass per output tile.  The operand pipeline runs across tiles: the first K tile of
+  // the workgroup's next output tile is requested while the last K tile of this one is
+  // being multiplied, and lands during the epilogue.
+  for (;;) {
+    int nvb = vb, nbm0 = 0, nbn0 = 0;
+    const bool has_next = next_tile(nvb, nbm0, nbn0);
+    const bf16_t* gpn[LPW];
+    if (has_next) sources(nbm0, nbn0, gpn);
 
-  if constexpr (Epi::kRowRuns) {
-    // Accumulator lane (li, lh) holds row m = 32 i + li, columns 32 j + 8 g + 4 lh + e.
-    // The finished bf16 values go through this wave's slice of the (now idle) operand
-    // stages, XOR-swizzled by 16-byte chunk, and leave as 16-byte stores: a wave-store
-    // covers whole 2 WTN-byte row segments instead of 2 bytes per lane.
-    __syncthreads();                                  // every wave is done reading the stages
-    constexpr int ROWB = WTN * 2;                     // bytes per staged row
-    constexpr int CPRW = WTN / 8;                     // 16-byte chunks per row
-    constexpr int RPLC = 256 / ROWB > 0 ? 256 / ROWB : 1;   // rows per 256-byte LDS line
-    constexpr bool POW2 = (CPRW & (CPRW - 1)) == 0;
-    static_assert(NW * WTM * ROWB <= S * STAGE_BYTES, "staging area");
-    static_assert((WTM * CPRW) % 64 == 0, "whole wave-stores");
-    // chunk position inside a row: XOR with the line index (power-of-two rows), else a rotation
-    auto swz = [](int row, int chunk) {
-      return POW2 ? (chunk ^ ((row / RPLC) & (CPRW - 1))) : (chunk + row) % CPRW;
-    };
-    unsigned char* cst = smem + wave * (WTM * ROWB);
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n0 = bn0 + wc * WTN + j * 32 + g * 8 + lh * 4;
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-          epi.apply4(n0, v);
-          bf16x4 o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = (bf16_t)v[e];
-          const int row = i * 32 + li, chunk = 4 * j + g;
-          *(bf16x4*)(cst + row * ROWB + (swz(row, chunk) << 4) + lh * 8) = o;
-        }
-      }
-#pragma unroll
-    for (int it = 0; it < WTM * CPRW / 64; ++it) {
-      const int idx = it * 64 + lane;
-      const int row = idx / CPRW, chunk = idx % CPRW;
-      const bf16x8 o = *(const bf16x8*)(cst + row * ROWB + (swz(row, chunk) << 4));
-      const int m = bm0 + wr * WTM + row, n0 = bn0 + wc * WTN + chunk * 8;
-      if (m < M && n0 < N) __builtin_nontemporal_store(o, (bf16x8*)epi.run8(m, n0));
-    }
-  } else {
+    f32x16 acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int j = 0; j < TN; ++j) {
-        const auto col = epi.col(bn0 + wc * WTN + j * 32 + li);
+      for (int j = 0; j < TN; ++j)
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int m0 = bm0 + wr * WTM + i * 32 + g * 8 + lh * 4;
-          float v[4] = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-          epi.store4(col, m0, v);
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    for (int kt = 0; kt < nkt; ++kt, ++g) {
+      if (kt > 0) {                                // K tile 0 was awaited and published before the previous epilogue
+        wait_vm<0>();
+        __builtin_amdgcn_s_barrier();
+      }
+      if (kt + 1 < nkt) issue(gp, kt + 1, (g + 1) & 1);
+      else if (has_next) issue(gpn, 0, (g + 1) & 1);
+      const unsigned char* st = smem + (g & 1) * STAGE_BYTES;
+      // Fragment reads run one 16-wide k-slice ahead of the MFMAs that consume them, in
+      // two register sets.  The scheduling groups below pin the instruction order the
+      // compiler would otherwise collapse into read-all / wait / multiply: after the first
+      // slice's reads, every read of slice ks+1 is paired with one MFMA of slice ks, so the
+      // LDS latency is spent under matrix work of the same wave.
+      constexpr int KS = BK / 16;
+      bf16x8 fa[2][TM], fb[2][TN];
+      auto load = [&](int ks, bf16x8 (&xa)[TM], bf16x8 (&xb)[TN]) {
+        const unsigned char* pa = st + a_row + (((2 * ks + lh) ^ a_x) << 4);
+        const unsigned char* pb = st + b_row + (((2 * ks + lh) ^ b_x) << 4);
+#pragma unroll
+        for (int i = 0; i < TM; ++i) xa[i] = *(const bf16x8*)(pa + i * TILE_STRIDE);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) xb[j] = *(const bf16x8*)(pb + j * TILE_STRIDE);
+      };
+      load(0, fa[0], fb[0]);
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        if (ks + 1 < KS) load(ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+          for (int j = 0; j < TN; ++j)
+            // row-run epilogues want a lane to hold consecutive n: D rows come from the A
+            // operand, so the weight fragment goes there (the operand layouts are alike)
+            acc[i][j] = Epi::kRowRuns
+                            ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[ks & 1][j], fa[ks & 1][i], acc[i][j], 0, 0, 0)
+                            : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+      }
+      constexpr int kDsRead = 0x100, kMfma = 0x008;
+      __builtin_amdgcn_sched_group_barrier(kDsRead, TM + TN, 0);
+#pragma unroll
+      for (int ks = 0; ks + 1 < KS; ++ks) {
+#pragma unroll
+        for (int r = 0; r < TM + TN; ++r) {
+          __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);
+        }
+        if (TM * TN > TM + TN) __builtin_amdgcn_sched_group_barrier(kMfma, TM * TN - (TM + TN), 0);
+      }
+      __builtin_amdgcn_sched_group_barrier(kMfma, TM * TN, 0);
+    }
+
+    // the next output tile's first K tile has landed (stage g & 1); every wave is done
+    // reading the stage just multiplied ((g - 1) & 1), which the epilogue may now reuse
+    wait_vm<0>();
+    __builtin_amdgcn_s_barrier();
+
+    if constexpr (Epi::kRowRuns) {
+      // Accumulator lane (li, lh) holds row m = 32 i + li, columns 32 j + 8 g + 4 lh + e.
+      // The finished bf16 values go, 32 rows at a time, through this wave's slice of the
+      // idle operand stage, swizzled by 16-byte chunk, and leave as 16-byte stores: a
+      // wave-store covers whole 2 WTN-byte row segments instead of 2 bytes per lane.
+      constexpr int ROWB = WTN * 2;                     // bytes per staged row
+      constexpr int CPRW = WTN / 8;                     // 16-byte chunks per row
+      constexpr int RPLC = 256 / ROWB > 0 ? 256 / ROWB : 1;   // rows per 256-byte LDS line
+      constexpr bool POW2 = (CPRW & (CPRW - 1)) == 0;
+      static_assert(NW * 32 * ROWB <= STAGE_BYTES, "staging area");
+      static_assert((32 * CPRW) % 64 == 0, "whole wave-stores");
+      // chunk position inside a row: XOR with the line index (power-of-two rows), else a rotation
+      auto swz = [](int row, int chunk) {
+        return POW2 ? (chunk ^ ((row / RPLC) & (CPRW - 1))) : (chunk + row) % CPRW;
+      };
+      unsigned char* cst = smem + ((g - 1) & 1) * STAGE_BYTES + wave * (32 * ROWB);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int gq = 0; gq < 4; ++gq) {
+            const int n0 = bn0 + wc * WTN + j * 32 + gq * 8 + lh * 4;
+            float v[4] = {acc[i][j][4 * gq], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]};
+            epi.apply4(n0, v);
+            bf16x4 o;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = (bf16_t)v[e];
+            *(bf16x4*)(cst + li * ROWB + (swz(li, 4 * j + gq) << 4) + lh * 8) = o;
+          }
+#pragma unroll
+        for (int it = 0; it < 32 * CPRW / 64; ++it) {
+          const int idx = it * 64 + lane;
+          const int row = idx / CPRW, chunk = idx % CPRW;
+          const bf16x8 o = *(const bf16x8*)(cst + row * ROWB + (swz(row, chunk) << 4));
+          const int m = bm0 + wr * WTM + i * 32 + row, n0 = bn0 + wc * WTN + chunk * 8;
+          if (m < M && n0 < N) __builtin_nontemporal_store(o, (bf16x8*)epi.run8(m, n0));
         }
       }
+    } else {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          const auto col = epi.col(bn0 + wc * WTN + j * 32 + li);
+#pragma unroll
+          for (int gq = 0; gq < 4; ++gq) {
+            const int m0 = bm0 + wr * WTM + i * 32 + gq * 8 + lh * 4;
+            float v[4] = {acc[i][j][4 * gq], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]};
+            epi.store4(col, m0, v);
+          }
+        }
+    }
+    if (!has_next) break;
+    // the staging slices are read out: the next tile's second K tile may overwrite that stage
+    __builtin_amdgcn_s_barrier();
+    vb = nvb; bm0 = nbm0; bn0 = nbn0;
+#pragma unroll
+    for (int j = 0; j < LPW; ++j) gp[j] = gpn[j];
   }
 }
 
@@ -342,7 +381,11 @@ static hipError_t run_dlds(const void* A, const void* Wt, int M, int N, int K, c
   }
   const int tiles_m = ceil_div(M, BM), tiles_n = ceil_div(N, BN);
   const long long total = (long long)tiles_m * tiles_n;
-  const unsigned grid = (unsigned)((total + 255) / 256 * 256);
+  // persistent: as many workgroups as the chip holds at once (by LDS: one of the large
+  // configurations per CU, two of the 128x128 one), each walking its share of the tiles
+  const long long padded = (total + 255) / 256 * 256;
+  const long long slots = 256LL * (smem > 80 * 1024 ? 1 : 2);
+  const unsigned grid = (unsigned)(padded < slots ? padded : slots);
   kern<<<grid, WR * WC * 64, smem, s>>>((const bf16_t*)A, (const bf16_t*)Wt, M, N, K, tiles_m, tiles_n, epi);
   return hipGetLastError();
 }
