@@ -168,7 +168,7 @@ def main():
                     help="also run one plain device copy of this size (a known-size kernel for scaling HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (no sharding, no collectives); use --gpus 1",
+        print("bench.py: the library runs on one GPU only (no sharding, no collectives); use --gpus 1",
               file=sys.stderr)
         sys.exit(2)
 
