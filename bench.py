@@ -155,6 +155,61 @@ def cache_restore_bench(args):
         "ops": out}))
 
 
+def hbm_ops_bench(args):
+    """Secondary measurement (--hbm-ops): the two HBM-bound operators of a step whose real
+    shapes are too small to show a rate, LayerNorm+modulate and the guidance + DDIM update,
+    timed at the real shape (latency) and on a scaled batch (GB/s).  One JSON line."""
+    import torch
+    import paper_2501_04012_amd as fc
+    torch.cuda.set_device(0)
+
+    def timed(fn, reps=args.steps):
+        for _ in range(args.warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    out = {}
+    g = torch.Generator(device="cuda").manual_seed(1)
+    # guidance + DDIM update: per element read x, eps_c, eps_u and write x = 16 bytes
+    coef = fc.fc_schedule_coefficients(fc.synth.Schedule(), 25)[0]
+    for label, n in (("cfg_ddim real (cfg5a: 4 x 16x32x32x4)", 4 * 65536), ("cfg_ddim real (cfg4 latent)", 13 * 60 * 90 * 16),
+                     ("cfg_ddim scaled (512 latents of 16x32x32x4)", 512 * 65536)):
+        x = torch.randn(n, device="cuda", generator=g)
+        ec = torch.randn(n, device="cuda", generator=g)
+        eu = torch.randn(n, device="cuda", generator=g)
+        ms = timed(lambda: fc.fc_op_cfg_ddim(x, ec, eu, None, n, 7.5, coef))
+        out[label] = {"ms": ms, "gbps": 16.0 * n / ms / 1e6}
+    # LayerNorm+modulate with the pending residual add: per element read x (4), read y (2),
+    # write x (4), write out (2) = 12 bytes; without the add: read x, write out = 6 bytes
+    for label, M, D in (("ln_modulate real (cfg4: 17776 x 3072)", 17776, 3072),
+                        ("ln_modulate scaled (cfg4 rows x 8)", 8 * 17776, 3072),
+                        ("ln_modulate real (cfg5a: 32768 x 1152)", 32768, 1152),
+                        ("ln_modulate scaled (cfg5a rows x 16)", 16 * 32768, 1152)):
+        x = torch.randn(M, D, device="cuda", generator=g)
+        y = (0.01 * torch.randn(M, D, device="cuda", generator=g)).to(torch.bfloat16)
+        sh = torch.randn(D, device="cuda", generator=g)
+        sc = torch.randn(D, device="cuda", generator=g)
+        o = torch.empty(M, D, device="cuda", dtype=torch.bfloat16)
+        ms = timed(lambda: fc.fc_op_layernorm_modulate(fc.FC_BF16, x, None, sh, sc, o, M, D, 1e-6))
+        ms_add = timed(lambda: fc.fc_op_layernorm_modulate(fc.FC_BF16, x, y, sh, sc, o, M, D, 1e-6))
+        out[label] = {"ms": ms, "gbps": 6.0 * M * D / ms / 1e6, "with_residual_add": {"ms": ms_add, "gbps": 12.0 * M * D / ms_add / 1e6}}
+    best = out["ln_modulate scaled (cfg4 rows x 8)"]["with_residual_add"]
+    print(json.dumps({
+        "metric": "LayerNorm+modulate (with residual add) GB/s on a scaled batch", "value": best["gbps"], "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": best["ms"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "hbm_ops"},
+        "roofline": {"kernel": "k_ln_modulate", "bound": "hbm", "achieved": best["gbps"], "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": best["gbps"] / PEAK_HBM_GBS, "traffic": None},
+        "ops": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -166,6 +221,8 @@ def main():
                     help="time the cache-restore entry points instead of a denoising workload")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this size (a known-size kernel for scaling HBM counters)")
+    ap.add_argument("--hbm-ops", action="store_true",
+                    help="time LayerNorm+modulate and the guidance+DDIM update at real and scaled shapes instead")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: the library runs on one GPU only (no sharding, no collectives); use --gpus 1",
@@ -181,6 +238,9 @@ def main():
         sys.exit(1)
     if args.cache_restore:
         cache_restore_bench(args)
+        return
+    if args.hbm_ops:
+        hbm_ops_bench(args)
         return
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]
