@@ -299,6 +299,19 @@ def main():
     fc.fc_profile_select(den.model, None)
     dom_launch_ms = dom_ms / dom_cnt
 
+    # per-step spread (after the timed region, no kernel bracketed): one event pair per step
+    # on the stream the steps run on; median and minimum over min(K, 20) steps
+    d_lat.copy_(d_lat0)
+    pairs = []
+    for _ in range(max(1, min(args.steps, 20))):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        den.step(d_lat, d_cond, d_null, w.schedule, w.step)
+        e1.record()
+        pairs.append((e0, e1))
+    torch.cuda.synchronize()
+    per_step = sorted(a.elapsed_time(b) for a, b in pairs)
+
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     forwards = R * (2 if use_cfg else 1)
     fl = synth.forward_flops(cfg)
@@ -355,6 +368,7 @@ def main():
         "config": {"workload": args.workload, "requests": R, "guidance_pair": use_cfg,
                    "tokens": cfg.seq_tokens, "hidden": cfg.hidden, "heads": cfg.heads, "depth": cfg.depth,
                    "attn_mode": "full3d_concat" if cfg.attn_mode else "factorized_cross"},
+        "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_min": per_step[0],
         "video_steps_per_s": R * 1e3 / ms_per_step,
         "tflops": tflops, "pct_bf16_peak": 100.0 * tflops / PEAK_BF16_TFLOPS,
         "step_tflop": step_flops / 1e12,

@@ -11,7 +11,9 @@ it; the denoiser is a U-Net or a diffusion transformer, and video models use
 spatial-temporal transformers.  The paper gives no further detail of the network,
 so the block below is the plain pre-LN adaLN diffusion transformer in its two
 video forms (factorized spatial/temporal attention + text cross-attention, or one
-attention over [text ; video] tokens).  Every choice the paper leaves open is
+attention over [text ; video] tokens; in the second form the text rows may carry
+modulation vectors of their own, a variant in which the two modalities are normalised
+and gated separately while sharing every other weight).  Every choice the paper leaves open is
 written out where it is taken.
 
 Evaluation is the textbook one: matmul for every linear layer, the full score
@@ -26,7 +28,10 @@ Pins (tests/test_oracle_*.py): brute-force attention loops, softmax row sums,
 uniform-key and single-key attention, token-permutation equivariance, frame
 locality of spatial / temporal attention, LayerNorm moments, GELU identities,
 sinusoid norms, patchify round trip, zero-modulation identity block, and an
-independently written einsum evaluation of the whole tiny network.
+independently written einsum evaluation of the whole tiny network.  Separate text
+modulation: equal text and video sets reproduce the shared form, zero gates of one
+modality leave exactly that modality's rows unchanged, and an independently written
+two-pass evaluation (text rows and video rows modulated in separate calls).
 The whole network with random weights has no printed worked example in the
 paper: beyond those pins its parity is unpinned by the paper.
 """
@@ -194,13 +199,23 @@ def _block_factorized(x, y, mod, W, pre, cfg):
 
 
 def _block_full3d(x, mod, W, pre, cfg, q_rows=None):
-    """x [L+N, D] (text rows first); mod [6D].  With q_rows the block is evaluated
-    for those rows only (attention still sees every key/value row)."""
+    """x [L+N, D] (text rows first); mod [6D], or [12D] when the text rows have their own
+    modulation (cfg.text_adaln): the first 6D chunks act on the video rows, the last 6D on
+    the L text rows.  With q_rows the block is evaluated for those rows only (attention
+    still sees every key/value row)."""
     D, h, eps = cfg.hidden, cfg.heads, cfg.ln_eps
     sh_a, sc_a, g_a, sh_m, sc_m, g_m = [mod[i * D:(i + 1) * D] for i in range(6)]
+    if getattr(cfg, "text_adaln", 0):
+        # every modulation vector becomes a per-row table: text set on rows < L, video set after
+        is_text = (np.arange(x.shape[0]) < cfg.text_len)[:, None]
+        tsh_a, tsc_a, tg_a, tsh_m, tsc_m, tg_m = [mod[(6 + i) * D:(7 + i) * D] for i in range(6)]
+        sh_a, sc_a, g_a = [np.where(is_text, tv, vv) for tv, vv in ((tsh_a, sh_a), (tsc_a, sc_a), (tg_a, g_a))]
+        sh_m, sc_m, g_m = [np.where(is_text, tv, vv) for tv, vv in ((tsh_m, sh_m), (tsc_m, sc_m), (tg_m, g_m))]
     u = modulate(layernorm(x, eps), sh_a, sc_a)
     a = self_attention(u, W[pre + "qkv_w"], W[pre + "qkv_b"], W[pre + "proj_w"], W[pre + "proj_b"],
                        h, q_rows=q_rows)
+    if q_rows is not None and getattr(cfg, "text_adaln", 0):
+        g_a, sh_m, sc_m, g_m = g_a[q_rows], sh_m[q_rows], sc_m[q_rows], g_m[q_rows]
     xr = x if q_rows is None else x[q_rows]
     xr = xr + g_a * a
     u = modulate(layernorm(xr, eps), sh_m, sc_m)

@@ -43,6 +43,7 @@ class ModelConfig:
     attn_mode: int = ATTN_FACTORIZED_CROSS
     dtype: int = DT_F32
     ln_eps: float = 1e-6
+    text_adaln: int = 0     # full-3D mode only: 1 = the text rows have modulation vectors of their own
 
     @property
     def spatial_tokens(self) -> int:
@@ -139,6 +140,7 @@ def weight_spec(cfg: ModelConfig) -> List[Tuple[str, Tuple[int, ...]]]:
     row-major so that y = x @ W + b.  The flat fp32 blob handed to the library is
     the concatenation of these tensors in this order."""
     D, M, te, dt, pd = cfg.hidden, cfg.mlp_dim, cfg.t_embed_dim, cfg.text_dim, cfg.patch_dim
+    nm3 = 12 if cfg.text_adaln else 6      # full-3D modulation chunks: video set (+ text set)
     spec: List[Tuple[str, Tuple[int, ...]]] = [
         ("t_w1", (te, D)), ("t_b1", (D,)), ("t_w2", (D, D)), ("t_b2", (D,)),
         ("y_w", (dt, D)), ("y_b", (D,)),
@@ -159,7 +161,7 @@ def weight_spec(cfg: ModelConfig) -> List[Tuple[str, Tuple[int, ...]]]:
             ]
         else:
             spec += [
-                (pre + "mod_w", (D, 6 * D)), (pre + "mod_b", (6 * D,)),
+                (pre + "mod_w", (D, nm3 * D)), (pre + "mod_b", (nm3 * D,)),
                 (pre + "qkv_w", (D, 3 * D)), (pre + "qkv_b", (3 * D,)),
                 (pre + "proj_w", (D, D)), (pre + "proj_b", (D,)),
             ]

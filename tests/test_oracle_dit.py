@@ -392,7 +392,24 @@ def independent_forward(cfg, W, lat, txt, t):
         x = np.concatenate([y, x.reshape(T * S, D)])
     for l in range(cfg.depth):
         P = f"blk{l}."
-        m = (sc @ W[P + "mod_w"] + W[P + "mod_b"]).reshape(6 if full3d else 9, D)
+        m = (sc @ W[P + "mod_w"] + W[P + "mod_b"]).reshape(-1, D)
+        assert len(m) == ((12 if cfg.text_adaln else 6) if full3d else 9)
+        if full3d and cfg.text_adaln:
+            # the two modalities are normalised, modulated and gated in separate calls
+            Lt, mv, mt = len(y), m[:6], m[6:]
+            u = np.concatenate([_ln(x[:Lt], cfg.ln_eps) * (1 + mt[1]) + mt[0],
+                                _ln(x[Lt:], cfg.ln_eps) * (1 + mv[1]) + mv[0]])
+            qkv = (u @ W[P + "qkv_w"] + W[P + "qkv_b"]).reshape(-1, 3, h, d)
+            pr = _sm(np.einsum("qhd,khd->hqk", qkv[:, 0], qkv[:, 1]) / math.sqrt(d))
+            a = np.einsum("hqk,khd->qhd", pr, qkv[:, 2]).reshape(-1, D) @ W[P + "proj_w"] + W[P + "proj_b"]
+            xt, xv = x[:Lt] + mt[2] * a[:Lt], x[Lt:] + mv[2] * a[Lt:]
+            parts = []
+            for xm, mm in ((xt, mt), (xv, mv)):
+                hd = (_ln(xm, cfg.ln_eps) * (1 + mm[4]) + mm[3]) @ W[P + "fc1_w"] + W[P + "fc1_b"]
+                hd = 0.5 * hd * (1 + np.tanh(math.sqrt(2 / math.pi) * (hd + 0.044715 * hd ** 3)))
+                parts.append(xm + mm[5] * (hd @ W[P + "fc2_w"] + W[P + "fc2_b"]))
+            x = np.concatenate(parts)
+            continue
         if full3d:
             u = _ln(x, cfg.ln_eps) * (1 + m[1]) + m[0]
             qkv = (u @ W[P + "qkv_w"] + W[P + "qkv_b"]).reshape(-1, 3, h, d)
@@ -438,6 +455,50 @@ def test_whole_tiny_network_against_independent_einsum_evaluation(depth, std, mo
     got = dit.forward(cfg, W, lat, txt, 500)
     want = independent_forward(cfg, W, lat, txt, 500)
     np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-11)
+
+
+# ---- separate modulation of the text rows (full-3D form)
+
+@pytest.mark.parametrize("depth,std", [(1, 0.02), (2, 0.3)])
+def test_text_adaln_against_independent_evaluation(depth, std):
+    cfg = _tiny(depth=depth, attn_mode=synth.ATTN_FULL3D_CONCAT, text_adaln=1)
+    W = synth.make_weights(cfg, 41, std=std)
+    assert W["blk0.mod_w"].shape == (cfg.hidden, 12 * cfg.hidden)
+    lat = synth.make_latent(cfg, 42)[0]; txt = synth.make_text(cfg, 43)[0]
+    np.testing.assert_allclose(dit.forward(cfg, W, lat, txt, 500), independent_forward(cfg, W, lat, txt, 500),
+                               rtol=1e-10, atol=1e-11)
+
+
+def test_text_adaln_with_equal_sets_is_the_shared_form():
+    shared = _tiny(depth=2, attn_mode=synth.ATTN_FULL3D_CONCAT)
+    split = _tiny(depth=2, attn_mode=synth.ATTN_FULL3D_CONCAT, text_adaln=1)
+    W = synth.make_weights(shared, 44, std=0.2)
+    W2 = dict(W)
+    for l in range(2):
+        W2[f"blk{l}.mod_w"] = np.concatenate([W[f"blk{l}.mod_w"]] * 2, axis=1)
+        W2[f"blk{l}.mod_b"] = np.concatenate([W[f"blk{l}.mod_b"]] * 2)
+    lat = synth.make_latent(shared, 45)[0]; txt = synth.make_text(shared, 46)[0]
+    np.testing.assert_allclose(dit.forward(split, W2, lat, txt, 300), dit.forward(shared, W, lat, txt, 300), atol=1e-13)
+
+
+@pytest.mark.parametrize("silent", ["text", "video"])
+def test_text_adaln_zero_gates_freeze_exactly_one_modality(silent):
+    cfg = _tiny(depth=1, attn_mode=synth.ATTN_FULL3D_CONCAT, text_adaln=1)
+    D, L = cfg.hidden, cfg.text_len
+    W = {k: v.astype(np.float64) for k, v in synth.make_weights(cfg, 47, std=0.2).items()}
+    rng = np.random.default_rng(48)
+    x = rng.standard_normal((L + cfg.video_tokens, D))
+    mod = rng.standard_normal(12 * D)
+    base = 6 * D if silent == "text" else 0
+    mod[base + 2 * D:base + 3 * D] = 0.0          # attention gate of that modality
+    mod[base + 5 * D:base + 6 * D] = 0.0          # MLP gate of that modality
+    out = dit._block_full3d(x, mod, W, "blk0.", cfg)
+    frozen, live = (slice(0, L), slice(L, None)) if silent == "text" else (slice(L, None), slice(0, L))
+    np.testing.assert_array_equal(out[frozen], x[frozen])
+    assert np.abs(out[live] - x[live]).min(axis=1).max() > 1e-3       # the other modality did move
+    # row sampling picks the same per-row vectors
+    rows = np.array([0, L - 1, L, L + 7])
+    np.testing.assert_allclose(dit._block_full3d(x, mod, W, "blk0.", cfg, q_rows=rows), out[rows], atol=1e-12)
 
 
 def test_fp32_oracle_agrees_with_fp64_oracle():
