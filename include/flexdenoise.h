@@ -69,6 +69,8 @@ typedef struct {
   int32_t attn_mode; /* FC_ATTN_* */
   int32_t dtype;     /* FC_F32 or FC_BF16 */
   float ln_eps;      /* LayerNorm epsilon (affine-free, biased variance) */
+  int32_t text_adaln;/* FC_ATTN_FULL3D_CONCAT only: 1 = the text rows are modulated and gated by a
+                        set of vectors of their own (variant); 0 = one set for all rows */
 } fc_model_config;
 
 /* Sampler.
@@ -119,7 +121,8 @@ int fc_model_weight_count(const fc_model* m, size_t* out);
  *     x_q_w[D,D] b  x_kv_w[D,2D] b  x_proj_w[D,D] b
  *     fc1_w[D,M] b  fc2_w[M,D] b
  *   per block, FULL3D_CONCAT:
- *     mod_w[D,6D] mod_b[6D]  (shift,scale,gate) x (attn, mlp)
+ *     mod_w[D,6D] mod_b[6D]  (shift,scale,gate) x (attn, mlp); with text_adaln [D,12D], [12D]:
+ *                            the video rows' six chunks, then the text rows' six
  *     qkv_w[D,3D] b  proj_w[D,D] b  fc1_w[D,M] b  fc2_w[M,D] b
  *   f_mod_w[D,2D] f_mod_b[2D]  (shift,scale) of the final layer
  *   f_w[D,p*p*C] f_b[p*p*C]

@@ -33,7 +33,7 @@ class FlexDenoiseError(RuntimeError):
 class fc_model_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("frames", "height", "width", "channels", "patch", "hidden", "heads",
                                          "mlp_dim", "depth", "text_len", "text_dim", "t_embed_dim",
-                                         "attn_mode", "dtype")] + [("ln_eps", C.c_float)]
+                                         "attn_mode", "dtype")] + [("ln_eps", C.c_float), ("text_adaln", C.c_int32)]
 
 
 class fc_schedule(C.Structure):
@@ -128,7 +128,7 @@ def _stream(stream) -> Optional[int]:
 def _cfg_struct(cfg: synth.ModelConfig) -> fc_model_config:
     return fc_model_config(cfg.frames, cfg.height, cfg.width, cfg.channels, cfg.patch, cfg.hidden, cfg.heads,
                            cfg.mlp_dim, cfg.depth, cfg.text_len, cfg.text_dim, cfg.t_embed_dim, cfg.attn_mode,
-                           cfg.dtype, cfg.ln_eps)
+                           cfg.dtype, cfg.ln_eps, cfg.text_adaln)
 
 
 def _sched_struct(s: synth.Schedule) -> fc_schedule:

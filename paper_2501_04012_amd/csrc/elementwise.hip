@@ -333,20 +333,29 @@ hipError_t launch_patch_embed(const float* latent, int R, int B, const float* Wp
 // ---------------------------------------------------------------- residual add + LayerNorm + modulate
 // One wave per row, the row held in registers (NCH 16-byte chunks per lane, all loads
 // issued before the first use).  If `y` is given, the pending branch output of the
-// previous linear layer is folded in first: x <- x + y (written back, fp32), then
+// previous linear layer is folded in first: x <- x + gate * y (gate NULL = ones; written
+// back, fp32), then
 //   out = (x - mean) * rsqrt(var + eps) * (1 + scale) + shift
 // with mean and centred variance as wave reductions (two passes over registers).
 // Output row r reads input row (r / out_rows_per_b) * in_rows_per_b + in_row_off +
-// r % out_rows_per_b, which lets the output head skip text rows.
+// r % out_rows_per_b, which lets the output head skip text rows.  Rows whose position in
+// their sequence (in_row_off + r % out_rows_per_b) is below alt_rows read shift, scale and
+// gate alt_off floats further on: the text rows' own modulation set.
 template <typename T, int NCH>
 __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, const T* __restrict__ y,
-                                                     const float* __restrict__ shift, const float* __restrict__ scale,
-                                                     T* __restrict__ out, int rows, int D, float eps, int in_rows_per_b,
-                                                     int out_rows_per_b, int in_row_off) {
+                                                     const float* __restrict__ gate, const float* __restrict__ shift,
+                                                     const float* __restrict__ scale, T* __restrict__ out, int rows, int D,
+                                                     float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off,
+                                                     int alt_rows, int alt_off) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = blockIdx.x * (blockDim.x >> 6) + wave;
   if (r >= rows) return;
-  const size_t in_r = (size_t)(r / out_rows_per_b) * in_rows_per_b + in_row_off + (r % out_rows_per_b);
+  const int pos = in_row_off + r % out_rows_per_b;
+  const size_t in_r = (size_t)(r / out_rows_per_b) * in_rows_per_b + pos;
+  if (pos < alt_rows) {                 // wave-uniform
+    if (gate) gate += alt_off;
+    if (scale) { scale += alt_off; shift += alt_off; }
+  }
   float* xr = x + in_r * D;
   f32x4 v[NCH];
 #pragma unroll
@@ -360,13 +369,16 @@ __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, cons
     for (int j = 0; j < NCH; ++j) {
       const int c = lane * 4 + j * 256;
       if (c < D) {
+        f32x4 yf;
         if constexpr (sizeof(T) == 2) {
           bf16x4 yv = *(const bf16x4*)(yr + c);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[j][e] += (float)yv[e];
+          for (int e = 0; e < 4; ++e) yf[e] = (float)yv[e];
         } else {
-          v[j] += *(const f32x4*)(yr + c);
+          yf = *(const f32x4*)(yr + c);
         }
+        if (gate) yf = yf * *(const f32x4*)(gate + c);
+        v[j] += yf;
         *(f32x4*)(xr + c) = v[j];
       }
     }
@@ -408,12 +420,13 @@ __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, cons
 }
 
 template <typename T>
-static hipError_t run_ln(float* x, const void* y, const float* shift, const float* scale, void* out, int rows, int D,
-                         float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off, hipStream_t s) {
+static hipError_t run_ln(float* x, const void* y, const float* gate, const float* shift, const float* scale, void* out,
+                         int rows, int D, float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off, int alt_rows,
+                         int alt_off, hipStream_t s) {
   dim3 grid(ceil_div(rows, 4));
 #define FC_LN(N)                                                                                                   \
-  k_ln_modulate<T, N><<<grid, 256, 0, s>>>(x, (const T*)y, shift, scale, (T*)out, rows, D, eps, in_rows_per_b,       \
-                                           out_rows_per_b, in_row_off)
+  k_ln_modulate<T, N><<<grid, 256, 0, s>>>(x, (const T*)y, gate, shift, scale, (T*)out, rows, D, eps, in_rows_per_b, \
+                                           out_rows_per_b, in_row_off, alt_rows, alt_off)
   if (D <= 256) FC_LN(1);
   else if (D <= 1280) FC_LN(5);
   else if (D <= 3072) FC_LN(12);
@@ -423,12 +436,15 @@ static hipError_t run_ln(float* x, const void* y, const float* shift, const floa
   return hipGetLastError();
 }
 
-hipError_t launch_ln_modulate(int bf16, float* x, const void* y, const float* shift, const float* scale, void* out,
-                              int rows, int D, float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off,
-                              hipStream_t s) {
+hipError_t launch_ln_modulate(int bf16, float* x, const void* y, const float* gate, const float* shift,
+                              const float* scale, void* out, int rows, int D, float eps, int in_rows_per_b,
+                              int out_rows_per_b, int in_row_off, int alt_rows, int alt_off, hipStream_t s) {
   if (rows == 0) return hipSuccess;
-  if (bf16) return run_ln<bf16_t>(x, y, shift, scale, out, rows, D, eps, in_rows_per_b, out_rows_per_b, in_row_off, s);
-  return run_ln<float>(x, y, shift, scale, out, rows, D, eps, in_rows_per_b, out_rows_per_b, in_row_off, s);
+  if (bf16)
+    return run_ln<bf16_t>(x, y, gate, shift, scale, out, rows, D, eps, in_rows_per_b, out_rows_per_b, in_row_off,
+                          alt_rows, alt_off, s);
+  return run_ln<float>(x, y, gate, shift, scale, out, rows, D, eps, in_rows_per_b, out_rows_per_b, in_row_off, alt_rows,
+                       alt_off, s);
 }
 
 // ---------------------------------------------------------------- guidance + DDIM update

@@ -169,7 +169,7 @@ size_t weight_count(const fc_model_config& c) {
   if (c.attn_mode == FC_ATTN_FACTORIZED_CROSS)
     per = D * 9 * D + 9 * D + 2 * (D * 3 * D + 3 * D + D * D + D) + (D * D + D) + (D * 2 * D + 2 * D) + (D * D + D);
   else
-    per = D * 6 * D + 6 * D + (D * 3 * D + 3 * D + D * D + D);
+    per = D * (c.text_adaln ? 12 : 6) * (D + 1) + (D * 3 * D + 3 * D + D * D + D);
   per += D * M + M + M * D + D;
   n += per * c.depth;
   n += D * 2 * D + 2 * D + D * pd + pd;
@@ -286,6 +286,11 @@ struct Ctx {
   // A branch's gated output sits in w.q, not yet added to the residual stream: the next
   // LayerNorm launch folds it in (x <- x + y) while it has the row in registers.
   mutable bool pending = false;
+  // Gate the fold applies to it (NULL: the projection's epilogue has applied it already).
+  // Used when the text rows have their own modulation set: the gate then depends on the row.
+  mutable const float* pending_gate = nullptr;
+  int alt_rows() const { return m->cfg.text_adaln ? m->cfg.text_len : 0; }
+  int alt_off() const { return 6 * m->cfg.hidden; }
 };
 
 struct ProfScope {        // records an event pair around the launches made in its lifetime
@@ -356,8 +361,9 @@ int prepare(const Ctx& c, const float* cond, const float* null_cond) {
 int ln_mod(const Ctx& c, const float* shift, const float* scale) {
   const fc_model* m = c.m;
   ProfScope ps(c, PC_LN_MODULATE);
-  HIP_TRY(launch_ln_modulate(m->bf16, c.w.x, c.pending ? c.w.q : nullptr, shift, scale, c.w.u, c.w.B * m->Ns,
-                             m->cfg.hidden, m->cfg.ln_eps, m->Ns, m->Ns, 0, c.s));
+  HIP_TRY(launch_ln_modulate(m->bf16, c.w.x, c.pending ? c.w.q : nullptr, c.pending ? c.pending_gate : nullptr, shift,
+                             scale, c.w.u, c.w.B * m->Ns, m->cfg.hidden, m->cfg.ln_eps, m->Ns, m->Ns, 0, c.alt_rows(),
+                             c.alt_off(), c.s));
   c.pending = false;
   return FC_OK;
 }
@@ -365,9 +371,11 @@ int ln_mod(const Ctx& c, const float* shift, const float* scale) {
 // Branch output projection: y = gate * (A W + b) into w.q (q, k, v are dead by then).
 int branch_out(const Ctx& c, int cat, const void* A, const Linear& L, const float* gate) {
   EpiParams ep;
-  ep.out = c.w.q; ep.ldo = c.m->cfg.hidden; ep.gate = gate;
+  const bool by_row = c.m->cfg.text_adaln != 0;      // the fold picks the row's gate instead
+  ep.out = c.w.q; ep.ldo = c.m->cfg.hidden; ep.gate = by_row ? nullptr : gate;
   int rc = linear(c, cat, EPI_GATE, A, L, c.w.B * c.m->Ns, ep);
   c.pending = rc == FC_OK;
+  c.pending_gate = by_row ? gate : nullptr;
   return rc;
 }
 
@@ -488,8 +496,8 @@ int run_step(const Ctx& c, float* latent, const fc_schedule* sched, int step, fl
   // head: LN + modulate on the video rows, Linear D -> p*p*C, scatter back to latent layout
   {
   ProfScope ps(c, PC_LN_MODULATE);
-  HIP_TRY(launch_ln_modulate(m->bf16, w.x, c.pending ? w.q : nullptr, w.fmod, w.fmod + D, w.u, w.B * m->N, D,
-                             cf.ln_eps, m->Ns, m->N, text_rows, c.s));
+  HIP_TRY(launch_ln_modulate(m->bf16, w.x, c.pending ? w.q : nullptr, c.pending ? c.pending_gate : nullptr, w.fmod,
+                             w.fmod + D, w.u, w.B * m->N, D, cf.ln_eps, m->Ns, m->N, text_rows, 0, 0, c.s));
   c.pending = false;
   }
   EpiParams ep;
@@ -542,6 +550,9 @@ int fc_model_create(const fc_model_config* cfg, fc_model** out) {
   if (c.attn_mode != FC_ATTN_FACTORIZED_CROSS && c.attn_mode != FC_ATTN_FULL3D_CONCAT)
     return fail(FC_ERR_SHAPE, "unknown attn_mode");
   if (c.dtype != FC_F32 && c.dtype != FC_BF16) return fail(FC_ERR_SHAPE, "unknown dtype");
+  if (c.text_adaln != 0 && c.text_adaln != 1) return fail(FC_ERR_SHAPE, "text_adaln must be 0 or 1");
+  if (c.text_adaln && c.attn_mode != FC_ATTN_FULL3D_CONCAT)
+    return fail(FC_ERR_SHAPE, "text_adaln needs the full-3D mode (text rows are not in the sequence otherwise)");
   const int hd = c.hidden / c.heads;
   const int ok_hd[] = {8, 16, 32, 64, 72, 96, 128};
   bool hd_ok = false;
@@ -560,7 +571,7 @@ int fc_model_create(const fc_model_config* cfg, fc_model** out) {
   m->Ns = m->N + (c.attn_mode == FC_ATTN_FULL3D_CONCAT ? c.text_len : 0);
   m->pd = c.patch * c.patch * c.channels;
   m->hd = hd;
-  m->nmod = c.attn_mode == FC_ATTN_FACTORIZED_CROSS ? 9 : 6;
+  m->nmod = c.attn_mode == FC_ATTN_FACTORIZED_CROSS ? 9 : c.text_adaln ? 12 : 6;
   *out = m;
   return FC_OK;
 }
@@ -809,7 +820,7 @@ int fc_op_layernorm_modulate(int32_t dtype, float* x, const void* y, const float
   if (!x || !out) return fail(FC_ERR_NULL, "NULL argument");
   if ((shift == nullptr) != (scale == nullptr)) return fail(FC_ERR_NULL, "shift and scale go together");
   if (M < 0 || D < 4 || D % 4 || D > 4096) return fail(FC_ERR_RANGE, "D must be a multiple of 4 in 4..4096");
-  HIP_TRY(launch_ln_modulate(dtype == FC_BF16, x, y, shift, scale, out, M, D, eps, M > 0 ? M : 1, M > 0 ? M : 1, 0,
+  HIP_TRY(launch_ln_modulate(dtype == FC_BF16, x, y, nullptr, shift, scale, out, M, D, eps, M > 0 ? M : 1, M > 0 ? M : 1, 0, 0, 0,
                              (hipStream_t)stream));
   return FC_OK;
 }

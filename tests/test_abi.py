@@ -82,6 +82,21 @@ def test_schedule_errors_are_status_codes(fc):
     np.testing.assert_allclose(coef[3], math.sqrt(1 - a_p - sg * sg), rtol=2e-6)
 
 
+def test_model_configuration_errors_and_weight_counts(fc):
+    from dataclasses import replace
+    tiny = synth.WORKLOADS["cfg1"].model
+    # separate text modulation exists only where the text rows are part of the sequence
+    with pytest.raises(fc.FlexDenoiseError) as e:
+        fc.fc_model_create(replace(tiny, attn_mode=synth.ATTN_FACTORIZED_CROSS, text_adaln=1))
+    assert e.value.status == -2
+    with pytest.raises(fc.FlexDenoiseError) as e:
+        fc.fc_model_create(replace(tiny, attn_mode=synth.ATTN_FULL3D_CONCAT, text_adaln=2))
+    assert e.value.status == -2
+    D = tiny.hidden
+    full = replace(tiny, attn_mode=synth.ATTN_FULL3D_CONCAT)
+    assert synth.weight_count(replace(full, text_adaln=1)) - synth.weight_count(full) == tiny.depth * 6 * D * (D + 1)
+
+
 def test_weight_spec_matches_library_count_formula():
     # closed-form parameter counts: cfg-2 block has 29 D^2 + biases; cfg-4 block 18 D^2 + biases
     c2 = synth.WORKLOADS["cfg2"].model

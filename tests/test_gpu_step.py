@@ -86,6 +86,43 @@ def test_small_model_with_16_latent_channels(fc, dtype):
     check(*got, *want, bf16=dtype == synth.DT_BF16)
 
 
+@pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
+def test_small_full3d_model_with_separate_text_modulation(fc, dtype):
+    """Variant: the text rows of the full-3D sequence are modulated and gated by their own
+    vectors (12 chunks per block).  Two blocks so that the text rows' gated updates feed the
+    video rows through the second attention; modulation weights large enough that the two
+    sets differ visibly; ragged sizes, guidance, two requests."""
+    cfg = synth.ModelConfig(frames=3, height=12, width=20, channels=4, patch=2, hidden=256, heads=4, mlp_dim=512,
+                            depth=2, text_len=26, text_dim=96, attn_mode=synth.ATTN_FULL3D_CONCAT, dtype=dtype,
+                            text_adaln=1)
+    w = synth.Workload("small_text_adaln", cfg, weight_seed=37, latent_seed=38, text_seed=39, null_seed=40, requests=2)
+    W = synth.make_weights(cfg, 37, std=0.08)
+    inputs = synth.workload_inputs(w)
+    got = run_step_gpu(fc, w, weights=W, inputs=inputs)
+    want = oracle_step(w, cfg, W, inputs, w.step)
+    check(*got, *want, bf16=dtype == synth.DT_BF16)
+    # the variant is live: giving the text rows the video rows' vectors changes the result
+    W_same = dict(W)
+    for l in range(cfg.depth):
+        for n in ("mod_w", "mod_b"):
+            a = W[f"blk{l}.{n}"]
+            half = a.shape[-1] // 2
+            W_same[f"blk{l}.{n}"] = np.concatenate([a[..., :half], a[..., :half]], axis=-1)
+    other = oracle_step(w, cfg, W_same, inputs, w.step)
+    assert rel_l2(other[1], want[1]) > 10 * (2e-2 if dtype == synth.DT_BF16 else F32_REL)
+
+
+def test_library_weight_counts_match_the_specification(fc):
+    tiny = synth.WORKLOADS["cfg1"].model
+    for cfg in (tiny, replace(tiny, attn_mode=synth.ATTN_FULL3D_CONCAT),
+                replace(tiny, attn_mode=synth.ATTN_FULL3D_CONCAT, text_adaln=1)):
+        m = fc.fc_model_create(cfg)
+        try:
+            assert fc.fc_model_weight_count(m) == synth.weight_count(cfg)
+        finally:
+            fc.fc_model_destroy(m)
+
+
 def test_cfg2_bf16_factorized_block(fc):
     w = synth.WORKLOADS["cfg2"]
     W = synth.make_weights(w.model, w.weight_seed)
