@@ -112,6 +112,29 @@ def test_small_full3d_model_with_separate_text_modulation(fc, dtype):
     assert rel_l2(other[1], want[1]) > 10 * (2e-2 if dtype == synth.DT_BF16 else F32_REL)
 
 
+@pytest.mark.parametrize("case", ["one_frame_one_text_token", "one_spatial_token", "full3d_two_tokens"])
+@pytest.mark.parametrize("dtype", [synth.DT_F32, synth.DT_BF16])
+def test_degenerate_sequence_lengths(fc, case, dtype):
+    """Sequences of length one: a softmax over a single key returns that key's value, so the
+    temporal (one frame), spatial (one patch per frame) and cross (one text token) branches
+    reduce to linear maps; the full-3D case attends over two tokens.  Guidance, three
+    requests (an odd batch)."""
+    shape = {"one_frame_one_text_token": dict(frames=1, height=8, width=12, text_len=1,
+                                              attn_mode=synth.ATTN_FACTORIZED_CROSS),
+             "one_spatial_token": dict(frames=5, height=2, width=2, text_len=3,
+                                       attn_mode=synth.ATTN_FACTORIZED_CROSS),
+             "full3d_two_tokens": dict(frames=1, height=2, width=2, text_len=1,
+                                       attn_mode=synth.ATTN_FULL3D_CONCAT)}[case]
+    cfg = synth.ModelConfig(channels=4, patch=2, hidden=256, heads=4, mlp_dim=512, depth=2, text_dim=96, dtype=dtype,
+                            **shape)
+    w = synth.Workload("degenerate", cfg, weight_seed=57, latent_seed=58, text_seed=59, null_seed=60, requests=3)
+    W = synth.make_weights(cfg, 57, std=0.08)
+    inputs = synth.workload_inputs(w)
+    got = run_step_gpu(fc, w, weights=W, inputs=inputs)
+    want = oracle_step(w, cfg, W, inputs, w.step)
+    check(*got, *want, bf16=dtype == synth.DT_BF16)
+
+
 def test_library_weight_counts_match_the_specification(fc):
     tiny = synth.WORKLOADS["cfg1"].model
     for cfg in (tiny, replace(tiny, attn_mode=synth.ATTN_FULL3D_CONCAT),
