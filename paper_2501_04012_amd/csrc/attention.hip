@@ -436,7 +436,9 @@ struct FlashCfg {
   static constexpr int KS = HDP / 16;        // k-steps of Q K^T
   static constexpr int CT = HDV / 32;        // O^T row tiles
   static constexpr int LDK = HDP + 8;        // LDS row of K tile (elements)
-  static constexpr int LDV = HDV + 8;        // LDS row of V tile
+  // LDS row of the V tile.  A transpose read's 32 lanes cover 4 consecutive key rows x 64
+  // bytes: the rows fall into disjoint bank ranges when the pitch is 64 or 192 bytes mod 256.
+  static constexpr int LDV = (HDV % 128 == 32 || HDV % 128 == 96) ? HDV : HDV + 32;
   static constexpr int K_ELEMS = 64 * LDK, V_ELEMS = 64 * LDV;
   static constexpr size_t SMEM = (size_t)2 * (K_ELEMS + V_ELEMS) * sizeof(bf16_t);
   static constexpr int CH = HD / 8;          // 16-byte chunks per K row
