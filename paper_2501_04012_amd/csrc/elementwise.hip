@@ -91,59 +91,99 @@ hipError_t launch_sinusoid(float t, int dim, float* out, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------- GEMV
-// out[l][n] = f_out( sum_k f_in(in[k]) * Wt[l][n][k] + bias[l][n] ), one wave per
-// output element, lanes striding K with 16-byte loads.  The input vector is
-// shared by all layers l (the adaLN layers of every block read the same SiLU(c)).
-template <typename T>
-__global__ void k_gemv(const float* __restrict__ in, int K, const T* __restrict__ Wt, const float* __restrict__ bias,
-                       float* __restrict__ out, int N, int in_silu, int out_silu, size_t w_layer_stride,
-                       size_t b_layer_stride, size_t out_layer_stride) {
-  extern __shared__ float s_in[];
+// out[l][n] = f_out( sum_k f_in(in[k]) * Wt[l][n][k] + bias[l][n] ): a wave owns NOUT
+// consecutive outputs, lanes stride K with 16-byte loads, the weight loads of all NOUT
+// rows of a K slice are in flight together.  The input vector is shared by all layers l
+// (the adaLN layers of every block read the same SiLU(c)); a workgroup stages it in LDS
+// once, 16-byte chunk q at position q ^ ((q >> 4) & 1) so that the two chunks a lane reads
+// per step (2 lane, 2 lane + 1) fall into distinct banks across 16 lanes.
+template <typename T, int NOUT>
+__global__ __launch_bounds__(256) void k_gemv(const float* __restrict__ in, int K, const T* __restrict__ Wt,
+                                              const float* __restrict__ bias, float* __restrict__ out, int N, int in_silu,
+                                              int out_silu, size_t w_layer_stride, size_t b_layer_stride,
+                                              size_t out_layer_stride) {
+  extern __shared__ __attribute__((aligned(16))) float s_in[];
+  constexpr int V = 16 / sizeof(T);          // weights per 16-byte load
+  const bool vec = K % V == 0;
   for (int k = threadIdx.x; k < K; k += blockDim.x) {
     float v = in[k];
-    s_in[k] = in_silu ? silu_f(v) : v;
+    const int q = k >> 2;
+    s_in[vec ? ((q ^ ((q >> 4) & 1)) << 2) + (k & 3) : k] = in_silu ? silu_f(v) : v;
   }
   __syncthreads();
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int n = blockIdx.x * (blockDim.x >> 6) + wave;
+  const int n0 = (blockIdx.x * (blockDim.x >> 6) + wave) * NOUT;
   const int l = blockIdx.y;
-  if (n >= N) return;
-  const T* w = Wt + l * w_layer_stride + (size_t)n * K;
-  float acc = 0.0f;
-  constexpr int V = 16 / sizeof(T);
-  if (K % V == 0) {
+  if (n0 >= N) return;
+  const T* w = Wt + l * w_layer_stride + (size_t)n0 * K;
+  float acc[NOUT];
+#pragma unroll
+  for (int o = 0; o < NOUT; ++o) acc[o] = 0.0f;
+  if (vec) {
     for (int k = lane * V; k < K; k += 64 * V) {
-      if constexpr (sizeof(T) == 2) {
-        bf16x8 wv = *(const bf16x8*)(w + k);
+      float x[V];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc += s_in[k + e] * (float)wv[e];
-      } else {
-        f32x4 wv = *(const f32x4*)(w + k);
+      for (int c = 0; c < V / 4; ++c) {
+        const int q = (k >> 2) + c;
+        const f32x4 xv = *(const f32x4*)(s_in + ((q ^ ((q >> 4) & 1)) << 2));
 #pragma unroll
-        for (int e = 0; e < 4; ++e) acc += s_in[k + e] * wv[e];
+        for (int e = 0; e < 4; ++e) x[4 * c + e] = xv[e];
+      }
+#pragma unroll
+      for (int o = 0; o < NOUT; ++o) {
+        if (n0 + o < N) {                      // wave-uniform
+          if constexpr (sizeof(T) == 2) {
+            const bf16x8 wv = *(const bf16x8*)(w + (size_t)o * K + k);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[o] += x[e] * (float)wv[e];
+          } else {
+            const f32x4 wv = *(const f32x4*)(w + (size_t)o * K + k);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[o] += x[e] * wv[e];
+          }
+        }
       }
     }
   } else {
-    for (int k = lane; k < K; k += 64) acc += s_in[k] * to_f32(w[k]);
+    for (int k = lane; k < K; k += 64)
+#pragma unroll
+      for (int o = 0; o < NOUT; ++o)
+        if (n0 + o < N) acc[o] += s_in[k] * to_f32(w[(size_t)o * K + k]);
   }
-  acc = wave_sum(acc);
-  if (lane == 0) {
-    float v = acc + bias[l * b_layer_stride + n];
-    out[l * out_layer_stride + n] = out_silu ? silu_f(v) : v;
+#pragma unroll
+  for (int o = 0; o < NOUT; ++o) {
+    const float a = wave_sum(acc[o]);
+    if (lane == 0 && n0 + o < N) {
+      float v = a + bias[l * b_layer_stride + n0 + o];
+      out[l * out_layer_stride + n0 + o] = out_silu ? silu_f(v) : v;
+    }
   }
+}
+
+template <typename T>
+static hipError_t run_gemv(const float* in, int K, const void* Wt, const float* bias, float* out, int N, int in_silu,
+                           int out_silu, int layers, size_t w_layer_stride, size_t b_layer_stride,
+                           size_t out_layer_stride, hipStream_t s) {
+  const size_t sh = ((size_t)K + 3) / 4 * 4 * sizeof(float) + 16;      // the chunk swap may touch one chunk past K
+  // 8 outputs per wave where that still leaves several workgroups per CU; else one each
+  if ((long long)ceil_div(N, 32) * layers >= 512)
+    k_gemv<T, 8><<<dim3(ceil_div(N, 32), layers), 256, sh, s>>>(in, K, (const T*)Wt, bias, out, N, in_silu, out_silu,
+                                                               w_layer_stride, b_layer_stride, out_layer_stride);
+  else
+    k_gemv<T, 1><<<dim3(ceil_div(N, 4), layers), 256, sh, s>>>(in, K, (const T*)Wt, bias, out, N, in_silu, out_silu,
+                                                              w_layer_stride, b_layer_stride, out_layer_stride);
+  return hipGetLastError();
 }
 
 hipError_t launch_gemv(int bf16, const float* in, int K, const void* Wt, const float* bias, float* out, int N,
                        int in_silu, int out_silu, int layers, size_t w_layer_stride, size_t b_layer_stride,
                        size_t out_layer_stride, hipStream_t s) {
   if (N == 0 || layers == 0) return hipSuccess;
-  dim3 grid(ceil_div(N, 4), layers);
-  size_t sh = (size_t)K * sizeof(float);
-  if (bf16) k_gemv<bf16_t><<<grid, 256, sh, s>>>(in, K, (const bf16_t*)Wt, bias, out, N, in_silu, out_silu,
-                                                 w_layer_stride, b_layer_stride, out_layer_stride);
-  else k_gemv<float><<<grid, 256, sh, s>>>(in, K, (const float*)Wt, bias, out, N, in_silu, out_silu,
-                                           w_layer_stride, b_layer_stride, out_layer_stride);
-  return hipGetLastError();
+  if (bf16)
+    return run_gemv<bf16_t>(in, K, Wt, bias, out, N, in_silu, out_silu, layers, w_layer_stride, b_layer_stride,
+                            out_layer_stride, s);
+  return run_gemv<float>(in, K, Wt, bias, out, N, in_silu, out_silu, layers, w_layer_stride, b_layer_stride,
+                         out_layer_stride, s);
 }
 
 // ---------------------------------------------------------------- patch embedding
