@@ -754,6 +754,221 @@ static hipError_t run_flash(const AttnParams& p, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------- few keys, many queries: keys and values resident in LDS
+// Text cross-attention: every query of a (batch, head) attends to the same nk <= 128
+// keys.  A workgroup stages them once (K [128][LDK], V [128][LDV], rows past nk zero) and
+// its 4 waves then walk a range of query rows, 32 per wave and pass, with no further
+// barrier: per pass a wave reads its Q fragments from global memory, forms S^T for all
+// keys (K fragments as the A operand, in the flash kernel's permuted row order so that P
+// is the B operand of the P V step as it stands), takes a plain two-pass softmax in
+// registers (all keys are present: no running reference), multiplies by V through
+// transpose reads and writes its 32 output rows.  The launch is bound by reading q and
+// writing o once; the staged keys are shared by rows_per_chunk queries instead of 128.
+template <int HD>
+__global__ __launch_bounds__(256, 2) void k_attn_kvres(AttnParams p, int chunks, int rows_per_chunk) {
+  using C = FlashCfg<HD>;
+  constexpr int NKP = 128;                            // padded key count
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_kv[];
+  bf16_t* Ks = (bf16_t*)smem_kv;                      // [128][LDK]
+  bf16_t* Vs = Ks + NKP * C::LDK;                     // [128][LDV]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int li = lane & 31, lh = lane >> 5;
+  int bid = blockIdx.x;
+  const int chunk = bid % chunks; bid /= chunks;
+  const int g = bid % p.groups; bid /= p.groups;
+  const int head = bid % p.heads;
+  const int b = bid / p.heads;
+  const int kb = key_batch(p, b);
+  const bf16_t* qbase = (const bf16_t*)p.q + ((size_t)b * p.heads + head) * (size_t)p.q_tokens * HD;
+  const bf16_t* kbase = (const bf16_t*)p.k + (((size_t)kb * p.heads + head) * (size_t)p.k_tokens +
+                                              (size_t)g * p.k_gstride) * HD;
+  const bf16_t* vbase = (const bf16_t*)p.v + (((size_t)kb * p.heads + head) * (size_t)p.k_tokens +
+                                              (size_t)g * p.k_gstride) * HD;
+
+  // ---- stage K and V: 16-byte chunks, zero for rows past nk and for the pad columns.  All
+  //      loads of a thread are issued before its first LDS store (one exposed latency).
+  {
+    constexpr int KC = C::HDP / 8, VC = C::HDV / 8;   // chunks per staged row, pads included
+    constexpr int KI = NKP * KC / 256, VI = NKP * VC / 256;
+    static_assert(NKP * KC % 256 == 0 && NKP * VC % 256 == 0, "whole passes of the workgroup");
+    bf16x8 zero;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) zero[e] = (bf16_t)0.0f;
+    bf16x8 rk[KI], rv[VI];
+#pragma unroll
+    for (int i = 0; i < KI; ++i) {
+      const int ch = tid + i * 256, row = ch / KC, kc = ch % KC;
+      rk[i] = zero;
+      if (row < p.nk && kc * 8 < HD) rk[i] = *(const bf16x8*)(kbase + (size_t)row * HD + kc * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < VI; ++i) {
+      const int ch = tid + i * 256, row = ch / VC, kc = ch % VC;
+      rv[i] = zero;
+      if (row < p.nk && kc * 8 < HD) rv[i] = *(const bf16x8*)(vbase + (size_t)row * HD + kc * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < KI; ++i) {
+      const int ch = tid + i * 256, row = ch / KC, kc = ch % KC;
+      *(bf16x8*)(Ks + row * C::LDK + kc * 8) = rk[i];
+    }
+#pragma unroll
+    for (int i = 0; i < VI; ++i) {
+      const int ch = tid + i * 256, row = ch / VC, kc = ch % VC;
+      *(bf16x8*)(Vs + row * C::LDV + kc * 8) = rv[i];
+    }
+  }
+  __syncthreads();
+
+  const int na = (p.nk + 31) / 32;                    // 32-key groups in use (1..4), wave-uniform
+  const int rem_last = p.nk - 32 * (na - 1);          // keys in the last of them (1..32)
+  // added to the last group's scores: -inf on the registers of keys past nk.  Register 4g+e
+  // of a group is its key 16(g/2) + 8h + 4(g%2) + e.
+  f32x16 pen, zero16;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    zero16[r] = 0.0f;
+    pen[r] = (16 * (r >> 3) + 8 * lh + 4 * ((r >> 2) & 1) + (r & 3) >= rem_last) ? -INFINITY : 0.0f;
+  }
+  const int prow = (li & 0x13) | ((li & 4) << 1) | ((li & 8) >> 1);   // li with bits 2 and 3 swapped
+  const int tr_row = (lane & 15) >> 2;
+  const int tr_col = ((lane >> 4) & 1) * 16 + (lane & 3) * 4;
+  bf16x2 ones;
+  ones[0] = (bf16_t)1.0f; ones[1] = (bf16_t)1.0f;
+  bf16_t* obase = (bf16_t*)p.out + (size_t)b * p.q_tokens * ((size_t)p.heads * HD) + (size_t)head * HD;
+
+  const int r_begin = chunk * rows_per_chunk;
+  const int r_end = min(p.nq, r_begin + rows_per_chunk);
+  // Q fragments: B operand, lane (i, h) holds Q[row i][16s + 8h .. +7].  The rows of the
+  // next pass are requested before the current pass is computed.
+  auto load_q = [&](int q0, bf16x8 (&dst)[C::KS]) {
+    int qi = q0 + li;
+    qi = qi < p.nq ? qi : p.nq - 1;
+    const bf16_t* qr = qbase + (size_t)(g * p.q_gstride + qi) * HD;
+#pragma unroll
+    for (int s = 0; s < C::KS; ++s) {
+      const int c0 = s * 16 + lh * 8;
+      if (c0 + 8 <= HD) dst[s] = *(const bf16x8*)(qr + c0);
+      else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) dst[s][e] = (bf16_t)0.0f;
+      }
+    }
+  };
+  // The passes of this wave, with the number of key groups a compile-time constant so that
+  // the four score chains and their LDS reads are scheduled together (no branch per group).
+  auto passes = [&](auto na_tag) {
+  constexpr int NA = decltype(na_tag)::value;
+  bf16x8 qn[C::KS];
+  if (r_begin + wave * 32 < r_end) load_q(r_begin + wave * 32, qn);
+  for (int q0 = r_begin + wave * 32; q0 < r_end; q0 += 4 * 32) {
+    bf16x8 qf[C::KS];
+#pragma unroll
+    for (int s = 0; s < C::KS; ++s) {
+      qf[s] = qn[s];
+      if (p.scale_log2 != 1.0f) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qf[s][e] = (bf16_t)((float)qf[s][e] * p.scale_log2);
+      }
+    }
+    if (q0 + 4 * 32 < r_end) load_q(q0 + 4 * 32, qn);
+
+    // ---- S^T = K Q^T for every key group in use.  Register 4g+e of group a is key
+    //      32a + 16(g/2) + 8h + 4(g%2) + e.
+    f32x16 sacc[NA];
+#pragma unroll
+    for (int s = 0; s < C::KS; ++s)
+#pragma unroll
+      for (int a = 0; a < NA; ++a) {
+        const bf16x8 kf = *(const bf16x8*)(Ks + (a * 32 + prow) * C::LDK + s * 16 + lh * 8);
+        sacc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], s == 0 ? zero16 : sacc[a], 0, 0, 0);
+      }
+    sacc[NA - 1] += pen;                              // only the last group can hold keys past nk
+    float mx = sacc[0][0];
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[a][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));           // finite: key 0 is valid
+
+    // ---- P = exp2(S - max) rounded to bf16 in B-operand order; O^T += V^T P^T
+    f32x16 oacc[C::CT];
+    float sum = 0.0f;
+#pragma unroll
+    for (int a = 0; a < NA; ++a) {
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          u32x4 pw;
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            bf16x2 pp;
+            pp[0] = (bf16_t)__builtin_amdgcn_exp2f(sacc[a][8 * s2 + 2 * x] - mx);
+            pp[1] = (bf16_t)__builtin_amdgcn_exp2f(sacc[a][8 * s2 + 2 * x + 1] - mx);
+            sum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, sum, false);
+            pw[x] = __builtin_bit_cast(unsigned int, pp);
+          }
+          const bf16x8 pk = __builtin_bit_cast(bf16x8, pw);
+#pragma unroll
+          for (int c = 0; c < C::CT; ++c) {
+            const bf16_t* src = Vs + (a * 32 + s2 * 16 + lh * 8 + tr_row) * C::LDV + c * 32 + tr_col;
+            const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)src);
+            const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(src + 4 * C::LDV));
+            const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            oacc[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pk, (a == 0 && s2 == 0) ? zero16 : oacc[c], 0, 0, 0);
+          }
+        }
+      }
+
+    // ---- O / l, token-major.  Lane (i, h) holds query column i, head dims 32c + 8g + 4h + e.
+    const float inv = 1.0f / (sum + __shfl_xor(sum, 32, 64));
+    const int qi = q0 + li;
+    if (qi < p.nq) {
+      bf16_t* orow = obase + (size_t)(g * p.q_gstride + qi) * ((size_t)p.heads * HD);
+#pragma unroll
+      for (int c = 0; c < C::CT; ++c)
+#pragma unroll
+        for (int gg = 0; gg < 4; ++gg) {
+          const int dd = 32 * c + 8 * gg + 4 * lh;
+          if (dd < HD) {
+            bf16x4 ov;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)(oacc[c][4 * gg + e] * inv);
+            *(bf16x4*)(orow + dd) = ov;
+          }
+        }
+    }
+  }
+  };
+  switch (na) {
+    case 1: passes(std::integral_constant<int, 1>{}); break;
+    case 2: passes(std::integral_constant<int, 2>{}); break;
+    case 3: passes(std::integral_constant<int, 3>{}); break;
+    default: passes(std::integral_constant<int, 4>{}); break;
+  }
+}
+
+template <int HD>
+static hipError_t run_kvres(const AttnParams& p, hipStream_t s) {
+  using C = FlashCfg<HD>;
+  constexpr size_t smem = (size_t)128 * (C::LDK + C::LDV) * sizeof(bf16_t);
+  const long long problems = (long long)p.B * p.heads * p.groups;
+  if (problems == 0) return hipSuccess;
+  // about 1024 workgroups (two rounds of two per CU; measured best among 256..2048) where the
+  // queries allow it; a chunk is a multiple of the 128 rows the four waves cover per pass
+  const int t128 = (p.nq + 127) / 128;
+  long long want = (1024 + problems - 1) / problems;
+  const int chunks = (int)(want < 1 ? 1 : want > t128 ? t128 : want);
+  const int rows_per_chunk = (t128 + chunks - 1) / chunks * 128;
+  const int used = (p.nq + rows_per_chunk - 1) / rows_per_chunk;
+  if (problems * used > 0x7fffffffLL) return hipErrorInvalidValue;
+  k_attn_kvres<HD><<<(unsigned)(problems * used), 256, smem, s>>>(p, used, rows_per_chunk);
+  return hipGetLastError();
+}
+
+// Keys and values resident: few keys shared by many queries (text cross-attention).
+static bool kvres_ok(const AttnParams& p) { return p.nk <= 128 && p.nq >= 512; }
+
 // The flash kernel needs unit-stride tokens inside a group, 16-byte aligned rows
 // (head dim a multiple of 8 elements) and head dims it is instantiated for.
 static bool flash_ok(const AttnParams& p) {
@@ -768,6 +983,10 @@ hipError_t launch_attention(int bf16, const AttnParams& p, int impl, hipStream_t
   // every kernel reads rows with 16-byte loads
   if ((((uintptr_t)p.q | (uintptr_t)p.k | (uintptr_t)p.v | (uintptr_t)p.out) & 15) != 0) return hipErrorInvalidValue;
   if (!bf16) return dispatch_plain<float>(p, impl != 1, s);
+  if (impl == 0 && flash_ok(p) && kvres_ok(p)) {
+    if (p.hd == 64) return run_kvres<64>(p, s);
+    if (p.hd == 72) return run_kvres<72>(p, s);
+  }
   if (impl == 0 && flash_ok(p)) {
     // One 32-query tile per wave (half the registers, twice the workgroups) when the key
     // sequence is short: the work per workgroup is then a few tiles and the launch lives

@@ -133,6 +133,18 @@ def test_attention_flash_bf16(fc, G, nq, nk, d, gain):
     assert max_abs(got, want) < 2.5e-2
 
 
+@pytest.mark.parametrize("G,nq,nk,d", [(3, 1000, 120, 72), (2, 4096, 26, 64), (1, 515, 128, 72), (2, 700, 1, 64),
+                                       (1, 2048, 97, 64), (5, 512, 33, 72), (1, 9000, 120, 72)])
+@pytest.mark.parametrize("gain", [1.0, 2.5])
+def test_attention_few_keys_many_queries_bf16(fc, G, nq, nk, d, gain):
+    """At most 128 keys shared by at least 512 queries (the text cross-attention shape): keys
+    and values stay in LDS, every key-group count 1..4, ragged query ranges and chunks."""
+    got, want = _attn_case(fc, G, nq, nk, d, gain, True, 0, scaled_q_rounding=True)
+    assert np.all(np.isfinite(got))
+    assert rel_l2(got, want) < 4e-3, (rel_l2(got, want), max_abs(got, want))
+    assert max_abs(got, want) < 2.5e-2
+
+
 @pytest.mark.parametrize("G,nq,nk,d,bf", [(2, 50, 70, 16, False), (3, 16, 16, 72, True), (1, 100, 130, 64, True),
                                           (2, 9, 5, 8, False), (1, 20, 40, 128, False)])
 def test_attention_plain(fc, G, nq, nk, d, bf):
