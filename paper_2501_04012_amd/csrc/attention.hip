@@ -220,15 +220,18 @@ static hipError_t run_short_strided(const AttnParams& p, hipStream_t s) {
 //   v_mfma_f32_16x16x16_bf16, whose A fragments (dim i, keys 4h .. 4h+3) are transpose
 //   reads of the row-major V tile.  All keys of a query are seen at once: plain two-pass
 //   softmax in registers, no running maximum.
-// A workgroup of 4 waves stages SB = 8 / KB neighbouring sequences ([SB][16 KB][PITCH] per
-// tensor, coalesced: for one t the SB rows are contiguous in memory) and has 8 work items
-// (sequence, query block), two per wave.  PITCH/8 is odd so that the 16 rows of a
-// fragment read fall into distinct bank groups.
+// A workgroup of 4 waves stages SB = ITEMS / KB neighbouring sequences ([SB][16 KB][PITCH]
+// per tensor, coalesced: for one t the SB rows are contiguous in memory) and has ITEMS work
+// items (sequence, query block), ITEMS / 4 per wave.  ITEMS = 4: at 28 KB of LDS five
+// workgroups share a CU and cover each other's load latency; with 8 items (55 KB, two per
+// CU) the launch was 9 % slower.  PITCH/8 is odd so that the 16 rows of a fragment read
+// fall into distinct bank groups.
 typedef __attribute__((ext_vector_type(4))) short i16x4;
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
-template <int HD, int KB>
+constexpr int kShortItems = 4;
+template <int HD, int KB, int ITEMS>
 struct ShortMfmaCfg {
-  static constexpr int SB = 8 / KB;                                      // sequences per workgroup
+  static constexpr int SB = ITEMS / KB;                                  // sequences per workgroup
   static constexpr int TP = 16 * KB;                                     // padded sequence length
   static constexpr int PITCH = ((HD / 8) % 2 == 1) ? HD : HD + 8;      // elements
   static constexpr int TILE = SB * TP * PITCH;                           // elements per tensor
@@ -237,9 +240,9 @@ struct ShortMfmaCfg {
   static constexpr int DT = (HD + 15) / 16;
 };
 
-template <int HD, int KB>
+template <int HD, int KB, int ITEMS>
 __global__ __launch_bounds__(256) void k_attn_short_mfma(AttnParams p) {
-  using C = ShortMfmaCfg<HD, KB>;
+  using C = ShortMfmaCfg<HD, KB, ITEMS>;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_sm[];
   bf16_t* qs = (bf16_t*)smem_sm;
   bf16_t* ks = qs + C::TILE;
@@ -280,7 +283,7 @@ __global__ __launch_bounds__(256) void k_attn_short_mfma(AttnParams p) {
   const int li = lane & 15, lh = lane >> 4;
   const int tr_r = li >> 2, tr_a = li & 3;
 #pragma unroll
-  for (int w = 0; w < 2; ++w) {
+  for (int w = 0; w < ITEMS / 4; ++w) {
     const int item = wave + 4 * w;                       // (sequence, query block)
     const int sq = item / KB, qb = item % KB;
     if (s0 + sq >= p.groups || 16 * qb >= Tn) continue;  // wave-uniform
@@ -364,10 +367,11 @@ static bool short_mfma_ok(const AttnParams& p) {
 
 template <int HD, int KB>
 static hipError_t run_short_mfma_kb(const AttnParams& p, hipStream_t s) {
-  using C = ShortMfmaCfg<HD, KB>;
+  constexpr int ITEMS = kShortItems;
+  using C = ShortMfmaCfg<HD, KB, ITEMS>;
   const long long blocks = (long long)p.B * p.heads * ((p.groups + C::SB - 1) / C::SB);
   if (blocks == 0) return hipSuccess;
-  auto kern = k_attn_short_mfma<HD, KB>;
+  auto kern = k_attn_short_mfma<HD, KB, ITEMS>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::SMEM);
