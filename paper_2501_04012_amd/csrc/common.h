@@ -100,6 +100,7 @@ struct Epilogue {
   FastDiv unp_S, unp_gw;       // EPI_UNPATCH
   FastDiv col_D, col_hd;       // EPI_HEADS, row-run form
   static constexpr bool kRowRuns = MODE != EPI_UNPATCH;
+  static constexpr bool kHasGate = MODE == EPI_GATE;
 
   // host side: fills the divisors the mode needs
   static Epilogue make(const EpiParams& p, int M, int N) {
@@ -153,10 +154,11 @@ struct Epilogue {
   // Row-run form.  Preconditions (checked by the dispatcher): Nvalid, ldo, hd and D are
   // multiples of 8; bias, gate and the output tensors are 16-byte aligned.
   // v: accumulators of columns n0..n0+3 (n0 % 4 == 0) of one row -> final values.
-  __device__ __forceinline__ void apply4(int n0, float (&v)[4]) const {
-    if (n0 >= Nvalid) return;                 // never stored
+  // lbias / lgate: LDS copies of bias[n0..] and gate[n0..] (the tile's slices; garbage-free
+  // for columns past Nvalid, which are never stored).
+  __device__ __forceinline__ void apply4(int n0, float (&v)[4], const float* lbias, const float* lgate) const {
     if (P.bias) {
-      const f32x4 b = *(const f32x4*)(P.bias + n0);
+      const f32x4 b = *(const f32x4*)lbias;
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] += b[e];
     }
@@ -165,15 +167,14 @@ struct Epilogue {
       for (int e = 0; e < 4; ++e) v[e] = gelu_tanh_f(v[e]);
     } else if constexpr (MODE == EPI_GATE) {
       if (P.gate) {
-        const f32x4 g = *(const f32x4*)(P.gate + n0);
+        const f32x4 g = *(const f32x4*)lgate;
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] *= g[e];
       }
     } else if constexpr (MODE == EPI_HEADS) {
-      if (P.which0 + (int)col_D.div((unsigned)n0) == 0) {
+      const float sc = (P.which0 + (int)col_D.div((unsigned)n0) == 0) ? P.qscale : 1.0f;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] *= P.qscale;
-      }
+      for (int e = 0; e < 4; ++e) v[e] *= sc;
     }
   }
   // Address of outputs (m, n0 .. n0+7), n0 % 8 == 0: one 16-byte run in every row-run mode.

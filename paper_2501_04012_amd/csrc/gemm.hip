@@ -61,6 +61,12 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
   static_assert(BM % RW == 0, "A/B boundary must fall between wave-loads");
 
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  // bias and gate of the current tile's BN columns, 1 KB each behind the two operand stages:
+  // fetched by DMA with the tile's first operand loads, read by the epilogue from LDS.  With
+  // loads from global memory in the epilogue every one of them was waited for in turn, behind
+  // the stores issued before it (the counter is shared): 10 000 cycles per 256x192 tile.
+  float* const sbias = (float*)(smem + S * STAGE_BYTES);
+  float* const sgate = sbias + 256;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave / WC, wc = wave % WC;
@@ -116,6 +122,17 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
     }
   };
 
+  auto issue_vectors = [&](int bn0) {
+    if constexpr (Epi::kRowRuns) {
+      int n = bn0 + lane * 4;
+      n = n < N ? n : 0;                           // columns past N are never stored
+      if (wave == 0 && epi.P.bias)
+        __builtin_amdgcn_global_load_lds((gbl_void*)(epi.P.bias + n), (lds_void*)sbias, 16, 0, 0);
+      if (Epi::kHasGate && wave == 1 && epi.P.gate)
+        __builtin_amdgcn_global_load_lds((gbl_void*)(epi.P.gate + n), (lds_void*)sgate, 16, 0, 0);
+    }
+  };
+
   // ---- fragment read offsets (bytes within a stage)
   const int ra = wr * WTM + li, rb = BM + wc * WTN + li;
   const int a_row = (ra / RPL) * 256 + (ra % RPL) * CPR * 16, a_x = (ra / RPL) % CPR;
@@ -154,6 +171,7 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
         wait_vm<0>();
         __builtin_amdgcn_s_barrier();
       }
+      if (kt == 0) issue_vectors(bn0);
       if (kt + 1 < nkt) issue(gp, kt + 1, (g + 1) & 1);
       else if (has_next) issue(gpn, 0, (g + 1) & 1);
       const unsigned char* st = smem + (g & 1) * STAGE_BYTES;
@@ -229,7 +247,7 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
           for (int gq = 0; gq < 4; ++gq) {
             const int n0 = bn0 + wc * WTN + j * 32 + gq * 8 + lh * 4;
             float v[4] = {acc[i][j][4 * gq], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]};
-            epi.apply4(n0, v);
+            epi.apply4(n0, v, sbias + (n0 - bn0), sgate + (n0 - bn0));
             bf16x4 o;
 #pragma unroll
             for (int e = 0; e < 4; ++e) o[e] = (bf16_t)v[e];
@@ -371,7 +389,7 @@ template <int BM, int BN, int BK, int WR, int WC, int S, int MODE>
 static hipError_t run_dlds(const void* A, const void* Wt, int M, int N, int K, const EpiParams& ep, hipStream_t s) {
   using Epi = Epilogue<bf16_t, MODE>;
   Epi epi = Epi::make(ep, M, N);
-  constexpr size_t smem = (size_t)S * (BM + BN) * BK * sizeof(bf16_t);
+  constexpr size_t smem = (size_t)S * (BM + BN) * BK * sizeof(bf16_t) + 2048;   // + bias and gate of a tile
   auto kern = k_gemm_dlds<BM, BN, BK, WR, WC, S, Epi>;
   static bool attr_set = false;
   if (!attr_set) {
