@@ -85,7 +85,17 @@ def cpu_baseline(w, weights, lat, cond):
         step_s = (t1 - t0) * (cfg.depth / d) * forwards
         sample = (f"fp32 oracle forward of one sample through {d} of {cfg.depth} blocks ({t1 - t0:.1f}s), "
                   f"scaled by depth and by {forwards} forwards per step")
-    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": int(cores), "kind": "oracle", "sample": sample}
+    cpu_model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return {"value": 1.0 / step_s, "unit": "steps/s", "cores": int(cores), "kind": "oracle", "sample": sample,
+            "host_cpus": os.cpu_count() or 0, "cpu_model": cpu_model}
 
 
 def cache_restore_bench(args):
