@@ -374,7 +374,8 @@ hipError_t launch_patch_embed(const float* latent, int R, int B, const float* Wp
 // One wave per row, the row held in registers (NCH 16-byte chunks per lane, all loads
 // issued before the first use).  If `y` is given, the pending branch output of the
 // previous linear layer is folded in first: x <- x + gate * y (gate NULL = ones; written
-// back, fp32), then
+// back in fp32 unless write_x is 0, which the last LayerNorm of a step passes: x is not read
+// after it), then
 //   out = (x - mean) * rsqrt(var + eps) * (1 + scale) + shift
 // with mean and centred variance as wave reductions (two passes over registers).
 // Output row r reads input row (r / out_rows_per_b) * in_rows_per_b + in_row_off +
@@ -386,7 +387,7 @@ __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, cons
                                                      const float* __restrict__ gate, const float* __restrict__ shift,
                                                      const float* __restrict__ scale, T* __restrict__ out, int rows, int D,
                                                      float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off,
-                                                     int alt_rows, int alt_off) {
+                                                     int alt_rows, int alt_off, int write_x) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int r = blockIdx.x * (blockDim.x >> 6) + wave;
   if (r >= rows) return;
@@ -419,7 +420,7 @@ __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, cons
         }
         if (gate) yf = yf * *(const f32x4*)(gate + c);
         v[j] += yf;
-        *(f32x4*)(xr + c) = v[j];
+        if (write_x) *(f32x4*)(xr + c) = v[j];     // not after the last block: x is not read again
       }
     }
   }
@@ -462,11 +463,11 @@ __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, cons
 template <typename T>
 static hipError_t run_ln(float* x, const void* y, const float* gate, const float* shift, const float* scale, void* out,
                          int rows, int D, float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off, int alt_rows,
-                         int alt_off, hipStream_t s) {
+                         int alt_off, int write_x, hipStream_t s) {
   dim3 grid(ceil_div(rows, 4));
 #define FC_LN(N)                                                                                                   \
   k_ln_modulate<T, N><<<grid, 256, 0, s>>>(x, (const T*)y, gate, shift, scale, (T*)out, rows, D, eps, in_rows_per_b, \
-                                           out_rows_per_b, in_row_off, alt_rows, alt_off)
+                                           out_rows_per_b, in_row_off, alt_rows, alt_off, write_x)
   if (D <= 256) FC_LN(1);
   else if (D <= 1280) FC_LN(5);
   else if (D <= 3072) FC_LN(12);
@@ -478,13 +479,14 @@ static hipError_t run_ln(float* x, const void* y, const float* gate, const float
 
 hipError_t launch_ln_modulate(int bf16, float* x, const void* y, const float* gate, const float* shift,
                               const float* scale, void* out, int rows, int D, float eps, int in_rows_per_b,
-                              int out_rows_per_b, int in_row_off, int alt_rows, int alt_off, hipStream_t s) {
+                              int out_rows_per_b, int in_row_off, int alt_rows, int alt_off, int write_x,
+                              hipStream_t s) {
   if (rows == 0) return hipSuccess;
   if (bf16)
     return run_ln<bf16_t>(x, y, gate, shift, scale, out, rows, D, eps, in_rows_per_b, out_rows_per_b, in_row_off,
-                          alt_rows, alt_off, s);
+                          alt_rows, alt_off, write_x, s);
   return run_ln<float>(x, y, gate, shift, scale, out, rows, D, eps, in_rows_per_b, out_rows_per_b, in_row_off, alt_rows,
-                       alt_off, s);
+                       alt_off, write_x, s);
 }
 
 // ---------------------------------------------------------------- guidance + DDIM update

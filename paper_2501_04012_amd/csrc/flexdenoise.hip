@@ -363,7 +363,7 @@ int ln_mod(const Ctx& c, const float* shift, const float* scale) {
   ProfScope ps(c, PC_LN_MODULATE);
   HIP_TRY(launch_ln_modulate(m->bf16, c.w.x, c.pending ? c.w.q : nullptr, c.pending ? c.pending_gate : nullptr, shift,
                              scale, c.w.u, c.w.B * m->Ns, m->cfg.hidden, m->cfg.ln_eps, m->Ns, m->Ns, 0, c.alt_rows(),
-                             c.alt_off(), c.s));
+                             c.alt_off(), 1, c.s));
   c.pending = false;
   return FC_OK;
 }
@@ -497,7 +497,7 @@ int run_step(const Ctx& c, float* latent, const fc_schedule* sched, int step, fl
   {
   ProfScope ps(c, PC_LN_MODULATE);
   HIP_TRY(launch_ln_modulate(m->bf16, w.x, c.pending ? w.q : nullptr, c.pending ? c.pending_gate : nullptr, w.fmod,
-                             w.fmod + D, w.u, w.B * m->N, D, cf.ln_eps, m->Ns, m->N, text_rows, 0, 0, c.s));
+                             w.fmod + D, w.u, w.B * m->N, D, cf.ln_eps, m->Ns, m->N, text_rows, 0, 0, 0, c.s));
   c.pending = false;
   }
   EpiParams ep;
@@ -820,7 +820,7 @@ int fc_op_layernorm_modulate(int32_t dtype, float* x, const void* y, const float
   if (!x || !out) return fail(FC_ERR_NULL, "NULL argument");
   if ((shift == nullptr) != (scale == nullptr)) return fail(FC_ERR_NULL, "shift and scale go together");
   if (M < 0 || D < 4 || D % 4 || D > 4096) return fail(FC_ERR_RANGE, "D must be a multiple of 4 in 4..4096");
-  HIP_TRY(launch_ln_modulate(dtype == FC_BF16, x, y, nullptr, shift, scale, out, M, D, eps, M > 0 ? M : 1, M > 0 ? M : 1, 0, 0, 0,
+  HIP_TRY(launch_ln_modulate(dtype == FC_BF16, x, y, nullptr, shift, scale, out, M, D, eps, M > 0 ? M : 1, M > 0 ? M : 1, 0, 0, 0, 1,
                              (hipStream_t)stream));
   return FC_OK;
 }
