@@ -2,6 +2,7 @@
 // batched GEMV (timestep MLP and adaLN modulation vectors), patch embedding,
 // residual add + LayerNorm + modulate, and the fused guidance + DDIM latent update.
 #include "common.h"
+#include <type_traits>
 
 namespace fc {
 
@@ -398,27 +399,58 @@ __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, cons
     if (scale) { scale += alt_off; shift += alt_off; }
   }
   float* xr = x + in_r * D;
-  f32x4 v[NCH];
+  // every load of the row (x, the pending y, gate, scale, shift) is issued before the first
+  // use: the kernel lives on loads in flight, not on arithmetic
+  // (for rows of up to 1280 elements; wider rows would need more registers than leave
+  // enough waves per SIMD, and read y, gate, scale and shift chunk by chunk instead)
+  constexpr bool BATCH = NCH <= 5;
+  constexpr int NB = BATCH ? NCH : 1;
+  typedef typename std::conditional<sizeof(T) == 2, bf16x4, f32x4>::type yvec;
+  f32x4 v[NCH], gv[NB], scv[NB], shv[NB];
+  yvec yv[NB];
+  const T* yr = y ? y + in_r * D : nullptr;
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
     const int c = lane * 4 + j * 256;
     v[j] = c < D ? *(const f32x4*)(xr + c) : f32x4{0, 0, 0, 0};
   }
+  if constexpr (BATCH) {
+    if (y) {
+#pragma unroll
+      for (int j = 0; j < NCH; ++j) {
+        const int c = lane * 4 + j * 256;
+        if (c < D) yv[j] = *(const yvec*)(yr + c);
+      }
+      if (gate) {
+#pragma unroll
+        for (int j = 0; j < NCH; ++j) {
+          const int c = lane * 4 + j * 256;
+          if (c < D) gv[j] = *(const f32x4*)(gate + c);
+        }
+      }
+    }
+    if (scale) {
+#pragma unroll
+      for (int j = 0; j < NCH; ++j) {
+        const int c = lane * 4 + j * 256;
+        if (c < D) { scv[j] = *(const f32x4*)(scale + c); shv[j] = *(const f32x4*)(shift + c); }
+      }
+    }
+  }
   if (y) {
-    const T* yr = y + in_r * D;
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
       const int c = lane * 4 + j * 256;
       if (c < D) {
-        f32x4 yf;
-        if constexpr (sizeof(T) == 2) {
-          bf16x4 yv = *(const bf16x4*)(yr + c);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) yf[e] = (float)yv[e];
-        } else {
-          yf = *(const f32x4*)(yr + c);
+        const int jb = BATCH ? j : 0;
+        if constexpr (!BATCH) {
+          yv[0] = *(const yvec*)(yr + c);
+          if (gate) gv[0] = *(const f32x4*)(gate + c);
         }
-        if (gate) yf = yf * *(const f32x4*)(gate + c);
+        f32x4 yf;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) yf[e] = (float)yv[jb][e];
+        if (gate) yf = yf * gv[jb];
         v[j] += yf;
         if (write_x) *(f32x4*)(xr + c) = v[j];     // not after the last block: x is not read again
       }
@@ -445,8 +477,8 @@ __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, cons
     if (c < D) {
       f32x4 w = (v[j] - mean) * rstd;
       if (scale) {
-        f32x4 sc = *(const f32x4*)(scale + c), sh = *(const f32x4*)(shift + c);
-        w = w * (1.0f + sc) + sh;
+        if constexpr (BATCH) w = w * (1.0f + scv[j]) + shv[j];
+        else w = w * (1.0f + *(const f32x4*)(scale + c)) + *(const f32x4*)(shift + c);
       }
       if constexpr (sizeof(T) == 2) {
         bf16x4 ov;
