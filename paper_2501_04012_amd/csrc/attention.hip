@@ -260,22 +260,35 @@ __global__ __launch_bounds__(256) void k_attn_short_mfma(AttnParams p) {
   const bf16_t* vg = (const bf16_t*)p.v + bh * HD;
 
   // ---- stage: rows t >= Tn are zero (V rows of masked keys must not hold NaN patterns)
+  //      All loads of a thread are issued before its first LDS store (one exposed latency).
   constexpr int CPR = HD / 8;
-  for (int ch = threadIdx.x; ch < C::TP * C::SB * CPR; ch += 256) {
+  constexpr int NCHK = C::TP * C::SB * CPR, NIT = (NCHK + 255) / 256;
+  f32x4 zq[NIT], zk[NIT], zv[NIT];
+#pragma unroll
+  for (int i = 0; i < NIT; ++i) {
+    const int ch = threadIdx.x + i * 256;
     const int c = ch % CPR, r = ch / CPR;
     const int sq = r % C::SB, t = r / C::SB;
-    const int loff = (sq * C::TP + t) * C::PITCH + c * 8;
-    f32x4 zq = {0.0f, 0.0f, 0.0f, 0.0f}, zk = zq, zv = zq;
-    if (t < Tn) {
+    zq[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f}; zk[i] = zq[i]; zv[i] = zq[i];
+    if (ch < NCHK && t < Tn) {
       int sg = s0 + sq; sg = sg < p.groups ? sg : p.groups - 1;   // sequences past the last are never stored
       const size_t goff = ((size_t)t * p.q_istride + sg) * HD + c * 8;
-      zq = *(const f32x4*)(qg + goff);
-      zk = *(const f32x4*)(kg + goff);
-      zv = *(const f32x4*)(vg + goff);
+      zq[i] = *(const f32x4*)(qg + goff);
+      zk[i] = *(const f32x4*)(kg + goff);
+      zv[i] = *(const f32x4*)(vg + goff);
     }
-    *(f32x4*)(qs + loff) = zq;
-    *(f32x4*)(ks + loff) = zk;
-    *(f32x4*)(vs + loff) = zv;
+  }
+#pragma unroll
+  for (int i = 0; i < NIT; ++i) {
+    const int ch = threadIdx.x + i * 256;
+    if (ch < NCHK) {
+      const int c = ch % CPR, r = ch / CPR;
+      const int sq = r % C::SB, t = r / C::SB;
+      const int loff = (sq * C::TP + t) * C::PITCH + c * 8;
+      *(f32x4*)(qs + loff) = zq[i];
+      *(f32x4*)(ks + loff) = zk[i];
+      *(f32x4*)(vs + loff) = zv[i];
+    }
   }
   __syncthreads();
 
