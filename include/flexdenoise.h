@@ -48,7 +48,9 @@ enum {
   FC_ERR_RANGE = -3,       /* step / k / batch outside its range */
   FC_ERR_WORKSPACE = -4,   /* workspace smaller than fc_workspace_bytes() */
   FC_ERR_DEVICE = -5,      /* a HIP call failed */
-  FC_ERR_UNSUPPORTED = -6, /* e.g. eta != 0 */
+  FC_ERR_UNSUPPORTED = -6, /* a combination the library does not implement (eta != 0 with the Euler
+                              sampler, more than 256 frames in a cache entry, a forced kernel whose
+                              shape conditions are not met) */
   FC_ERR_STATE = -7        /* weights not set yet */
 };
 
@@ -195,6 +197,10 @@ const char* fc_last_error(void);
  * fc_profile_category_name(i).  fc_profile_categories() returns the count, not a status.
  * fc_profile_select() restricts the brackets to one category (-1: all, the default), so
  * that a timed run carries the events of the kernel of interest only. */
+/* The category names in index order, separated by single spaces. */
+#define FC_PROFILE_CATEGORY_NAMES                                                          \
+  "gemm_qkv gemm_proj gemm_fc1 gemm_fc2 gemm_other attn_spatial attn_temporal attn_cross " \
+  "attn_full3d ln_modulate patch_embed timestep_modulation cfg_ddim other"
 int fc_profile_enable(fc_model* m, int32_t enable);
 int fc_profile_select(fc_model* m, int32_t category);
 int fc_profile_categories(void);

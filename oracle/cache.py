@@ -113,7 +113,10 @@ def alpha_least_squares(first_s, keys_s, diff_base) -> float:
     diff_base [n, F...] -> the scalar of Eq. 2."""
     d_s = np.asarray(keys_s, dtype=np.float64) - np.asarray(first_s, dtype=np.float64)[None]
     d_b = np.asarray(diff_base, dtype=np.float64)
-    return float((d_s * d_b).sum() / (d_b * d_b).sum())
+    den = float((d_b * d_b).sum())
+    if den == 0.0:            # Diff_base == 0: Eq. 2 is indeterminate, first + alpha * 0 does not depend on alpha
+        return 0.0
+    return float((d_s * d_b).sum() / den)
 
 
 def decompress(first, diff_base, alpha, extra, src):

@@ -19,8 +19,8 @@ Readings the paper leaves open, as taken here:
     and the last step goes to abar_prev = 1 (it returns the x0 estimate).
   * eta = 0: no noise is drawn, the update is a deterministic function of
     (x_t, eps).  eta > 0 (the paper changes the denoising seed after a retrieval to keep
-    outputs diverse, Appendix "Limitations"/discussion of homogenization, which needs a
-    sampler that draws noise): the DDIM family's stochastic member,
+    outputs diverse, Sec. 7 "Discussions and Related Works", which needs a sampler that
+    draws noise): the DDIM family's stochastic member,
       sigma = eta sqrt((1-abar_prev)/(1-abar_t)) sqrt(1 - abar_t/abar_prev),
       x_prev = sqrt(abar_prev) x0 + sqrt(1 - abar_prev - sigma^2) eps + sigma z,
     z standard normal.  z is not drawn from a stateful generator but computed from
@@ -45,8 +45,9 @@ the way it combines eps.
 
 Pins of the noise path: the three published known-answer vectors of Philox4x32-10, the
 moments of the generated normals, eta = 0 equals the deterministic update, eta = 1
-equals the ancestral (posterior-variance) step, and the variance bookkeeping
-(1 - abar_prev - sigma^2) + sigma^2 = 1 - abar_prev.
+equals the ancestral step typed in its posterior-mean form (alpha, beta, beta~ of the
+two visited timesteps; not through ddim_sigma), sigma linear in eta, and a Monte Carlo
+check that the step keeps the marginal variance 1 - abar_prev for any eta.
 
 Pins (tests/test_oracle_sampler.py): closed-form schedule values, monotonicity,
 exact recovery x_prev = sqrt(abar_prev) x0 + sqrt(1-abar_prev) eps* when the

@@ -13,7 +13,7 @@ namespace fc {
 // the pixel.  Masks: pixel i is bit i % 8 of byte i / 8.  VEC: channels % 4 == 0 and all
 // pointers 16-byte aligned, one thread per 4 channels; otherwise one thread per element.
 template <bool VEC>
-__global__ void k_stitch(const float* __restrict__ x_obj, const float* __restrict__ x_bg,
+__global__ void k_stitch(const float* x_obj, const float* x_bg,      // either may be `out` itself: no __restrict__
                          const uint8_t* __restrict__ m_obj, const uint8_t* __restrict__ m_bg, float* out,
                          long long pixels, int channels) {
   const int per_pixel = VEC ? channels / 4 : channels;
@@ -103,7 +103,9 @@ __global__ __launch_bounds__(64) void k_alpha_final(const double* __restrict__ p
   if (threadIdx.x != 0) return;
   double num = 0.0, den = 0.0;
   for (int b = 0; b < kRedBlocks; ++b) { num += partial[2 * b]; den += partial[2 * b + 1]; }
-  alpha_out[0] = (float)(num / den);
+  // Diff_base identically zero: every alpha fits equally well and the restored frames do not
+  // depend on it; the minimum-norm choice is 0
+  alpha_out[0] = den > 0.0 ? (float)(num / den) : 0.0f;
 }
 
 hipError_t launch_alpha(const float* first_s, const float* keys_s, const float* diff_base, int n_base, long long F,

@@ -468,8 +468,9 @@ int run_step(const Ctx& c, float* latent, const fc_schedule* sched, int step, fl
   const int text_rows = cf.attn_mode == FC_ATTN_FULL3D_CONCAT ? cf.text_len : 0;
   {
   ProfScope ps(c, PC_PATCH_EMBED);
+  // an fp32 model keeps fp32 arithmetic: the matrix-core kernel (bf16 high/low splits) is for bf16 models only
   HIP_TRY(launch_patch_embed(latent, c.R, w.B, m->p_w, m->p_b, m->pos_sp, m->pos_t, w.x, cf.frames, cf.height,
-                             cf.width, cf.channels, cf.patch, D, m->Ns, text_rows, 0, c.s));
+                             cf.width, cf.channels, cf.patch, D, m->Ns, text_rows, m->bf16 ? 0 : 1, c.s));
   if (text_rows)
     HIP_TRY(launch_act_to_f32_rows(m->bf16, w.y, w.x, w.B * cf.text_len, D, cf.text_len, m->Ns, 0, c.R, c.use_cfg,
                                    c.s));
@@ -523,10 +524,15 @@ int check_call(fc_model* m, const float* latent, const float* cond, const fc_sch
   int rc = schedule_check(sched);
   if (rc != FC_OK) return rc;
   if (R < 1) return fail(FC_ERR_RANGE, "batch_requests must be >= 1");
+  const long long B = (long long)R * (use_cfg ? 2 : 1);
+  if (B * m->Ns > (long long)INT32_MAX / 4) return fail(FC_ERR_RANGE, "batch too large");
+  // the epilogues split a row index m into (batch row, token) by multiply-shift, exact while
+  // m * divisor < 2^40 with m < B * Ns and the divisor Ns (q/k/v scatter) or T * S (un-patchify)
+  if (B * m->Ns * m->Ns >= (1ll << 40))
+    return fail(FC_ERR_RANGE, "batch_requests * tokens^2 must stay below 2^40");
   if (((uintptr_t)workspace & 255) != 0) return fail(FC_ERR_WORKSPACE, "workspace must be 256-byte aligned");
   Workspace w = carve(m, R, use_cfg, (unsigned char*)workspace);
   if (w.bytes > workspace_bytes) return fail(FC_ERR_WORKSPACE, "workspace smaller than fc_workspace_bytes()");
-  if ((long long)w.B * m->Ns > (long long)INT32_MAX / 4) return fail(FC_ERR_RANGE, "batch too large");
   ctx->m = m; ctx->w = w; ctx->R = R; ctx->use_cfg = use_cfg; ctx->s = (hipStream_t)stream;
   return FC_OK;
 }

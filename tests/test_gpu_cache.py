@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 
 from oracle import cache as ocache
+from oracle import sampler
 from paper_2501_04012_amd import synth
 from util import dev, host, record, rel_l2
 
@@ -141,7 +142,6 @@ def test_entry_round_trip_feeds_a_resume(fc):
     restored exactly (up to fp32 rounding) from first frame + alpha * base, stitched with
     a second cache, and resumed; the result equals resuming the oracle's stitched latent."""
     torch = _torch()
-    from oracle import sampler
     w = synth.WORKLOADS["cfg5b"]
     cfg = w.model
     W = synth.make_weights(cfg, w.weight_seed)
@@ -165,7 +165,10 @@ def test_entry_round_trip_feeds_a_resume(fc):
     x = torch.empty((1, T, H, Wd, C), device="cuda:0")
     fc.fc_cache_stitch(x_obj, x_bg, dev(mo), None, x, T * H * Wd, C)
     torch.cuda.synchronize()
-    want_obj = ocache.decompress(first_s.astype(np.float64), diff_base.astype(np.float64), alpha, None, list(range(T)))
+    want_alpha = ocache.alpha_least_squares(first_s, keys_s, diff_base)      # the oracle's own coefficient
+    assert abs(alpha - want_alpha) <= 2.0 ** -22 * abs(want_alpha)
+    want_obj = ocache.decompress(first_s.astype(np.float64), diff_base.astype(np.float64), want_alpha, None,
+                                 list(range(T)))
     want_x = ocache.stitch(want_obj, lat[2].astype(np.float64), mo)[None]
     assert rel_l2(host(x), want_x) < 1e-6
     den = fc.Denoiser(cfg, W, 1, True)
@@ -184,7 +187,8 @@ def test_entry_round_trip_feeds_a_resume(fc):
 def test_resume_ex_exports_the_key_steps(fc):
     """Hit at step 10 of the tiny configuration: the latents after steps 15, 20 and 25 are
     handed out; each equals a resume that stops there (same kernels, same order: bit for
-    bit), and the final latent equals the plain resume."""
+    bit) and the latent the oracle's loop holds after that step, and the final latent equals
+    the plain resume."""
     torch = _torch()
     w = synth.WORKLOADS["cfg5b"]
     cfg = w.model
@@ -206,6 +210,16 @@ def test_resume_ex_exports_the_key_steps(fc):
             if s in (15, 20, 25):
                 torch.cuda.synchronize()
                 assert torch.equal(exports[(s - 15) // 5], c), s
+        # the exported latents are the ones the oracle's loop passes through after those steps
+        # (free-running from the same stored latents; Sec. 4.2.4: these are what gets inserted)
+        seen = {}
+        want_final = sampler.denoise_resume(cfg, W, lat, cond, null, w.schedule, 10,
+                                            on_step=lambda s, x: seen.__setitem__(s, np.array(x)))
+        for e, s in enumerate((15, 20, 25)):
+            err = rel_l2(host(exports[e]), seen[s])
+            record(step=float(s), exported_latent_rel_l2=err)
+            assert err <= 1e-3, (s, err)
+        assert rel_l2(host(a), want_final) <= 1e-3
         # argument checks
         for steps in ([10], [51], [20, 15], [15, 15]):
             with pytest.raises(fc.FlexDenoiseError) as e:

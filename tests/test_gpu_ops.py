@@ -7,7 +7,7 @@ import pytest
 
 from oracle import dit, sampler
 from paper_2501_04012_amd import synth
-from util import dev, host, max_abs, rel_l2
+from util import dev, host, max_abs, record, rel_l2
 
 pytestmark = pytest.mark.gpu
 BF = synth.round_to_bf16
@@ -98,10 +98,11 @@ def test_linear_gated_branch_then_residual_layernorm(fc, dtype, gated):
 # --------------------------------------------------------------------------- attention
 
 def _attn_case(fc, G, nq, nk, d, gain, bf, impl, scaled_q_rounding=False):
-    """scaled_q_rounding: the MFMA flash kernel consumes bf16(q * scale * log2 e) (inside a
-    step the QKV epilogue produces exactly that from fp32; the stand-alone operator has to
-    round its bf16 input a second time).  The oracle is then fed that same rounded query,
-    so the comparison measures the kernel's arithmetic and not the input conversion."""
+    """Returns (got, want): want is the oracle on the inputs the entry point receives.
+    With scaled_q_rounding a third value is returned, the oracle on the query the MFMA flash
+    kernel actually multiplies: it consumes bf16(q * scale * log2 e) (inside a step the QKV
+    epilogue produces exactly that from fp32; the stand-alone operator has to round its
+    bf16 input a second time), so that comparison measures the kernel's arithmetic alone."""
     torch = _torch()
     qs, ks, vs = [], [], []
     for g in range(G):
@@ -110,39 +111,50 @@ def _attn_case(fc, G, nq, nk, d, gain, bf, impl, scaled_q_rounding=False):
     q, k, v = np.stack(qs), np.stack(ks), np.stack(vs)
     if bf:
         q, k, v = BF(q), BF(k), BF(v)
-    q_seen = q
-    if scaled_q_rounding:
-        c = np.float32(1.4426950408889634 / math.sqrt(d))
-        q_seen = BF(q.astype(np.float32) * c).astype(np.float64) / np.float64(c)
-    want = dit.attention(np.asarray(q_seen, dtype=np.float64), k.astype(np.float64), v.astype(np.float64))
+    want = dit.attention(np.asarray(q, dtype=np.float64), k.astype(np.float64), v.astype(np.float64))
     out = torch.full((G, nq, d), float("nan"), dtype=torch.bfloat16 if bf else torch.float32, device="cuda:0")
     fc.fc_op_attention(fc.FC_BF16 if bf else fc.FC_F32, dev(q, bf), dev(k, bf), dev(v, bf), out, G, nq, nk, d, impl)
     torch.cuda.synchronize()
-    return host(out), want
+    if not scaled_q_rounding:
+        return host(out), want
+    c = np.float32(1.4426950408889634 / math.sqrt(d))
+    q_seen = BF(q.astype(np.float32) * c).astype(np.float64) / np.float64(c)
+    return host(out), want, dit.attention(q_seen, k.astype(np.float64), v.astype(np.float64))
+
+
+def _check_flash(got, want, want_seen, gain):
+    """Two comparisons.  (1) Against the oracle on the raw inputs, at the parity bar of a
+    step (rel-L2 <= 1e-2, max-abs <= 5e-2).  The second rounding of an already-bf16 query
+    moves a score s by up to |s| 2^-9; at gain 4 (scores of +-60) that alone moves outputs by
+    more than 5e-2, so there the bound is widened by that effect, measured between the two
+    oracle evaluations.  (2) Against the oracle on the query the kernel multiplies, tighter."""
+    assert np.all(np.isfinite(got))
+    rounding_effect = max_abs(want_seen, want)
+    record(gain=gain, rel_l2_raw=rel_l2(got, want), max_abs_raw=max_abs(got, want),
+           rel_l2_kernel=rel_l2(got, want_seen), max_abs_kernel=max_abs(got, want_seen),
+           q_rounding_effect=rounding_effect)
+    assert rel_l2(got, want) <= 1e-2, (rel_l2(got, want), max_abs(got, want))
+    assert max_abs(got, want) <= 5e-2 + (rounding_effect if gain > 2.5 else 0.0)
+    assert rel_l2(got, want_seen) < 4e-3, (rel_l2(got, want_seen), max_abs(got, want_seen))
+    assert max_abs(got, want_seen) < 2.5e-2
 
 
 @pytest.mark.parametrize("G,nq,nk,d", [(3, 300, 333, 64), (2, 64, 64, 64), (1, 1, 1, 64), (2, 257, 120, 72),
                                        (1, 700, 1000, 64), (4, 256, 256, 72), (1, 33, 7, 72), (2, 600, 333, 64),
                                        (1, 1100, 1000, 64), (2, 513, 129, 64),
                                        (1, 4200, 650, 64)])      # long enough for the 8-wave workgroup, ragged both ways
-@pytest.mark.parametrize("gain", [1.0, 2.5])
+@pytest.mark.parametrize("gain", [1.0, 2.5, 4.0])
 def test_attention_flash_bf16(fc, G, nq, nk, d, gain):
-    got, want = _attn_case(fc, G, nq, nk, d, gain, True, 0, scaled_q_rounding=True)
-    assert np.all(np.isfinite(got))
-    assert rel_l2(got, want) < 4e-3, (rel_l2(got, want), max_abs(got, want))
-    assert max_abs(got, want) < 2.5e-2
+    _check_flash(*_attn_case(fc, G, nq, nk, d, gain, True, 0, scaled_q_rounding=True), gain)
 
 
 @pytest.mark.parametrize("G,nq,nk,d", [(3, 1000, 120, 72), (2, 4096, 26, 64), (1, 515, 128, 72), (2, 700, 1, 64),
                                        (1, 2048, 97, 64), (5, 512, 33, 72), (1, 9000, 120, 72)])
-@pytest.mark.parametrize("gain", [1.0, 2.5])
+@pytest.mark.parametrize("gain", [1.0, 2.5, 4.0])
 def test_attention_few_keys_many_queries_bf16(fc, G, nq, nk, d, gain):
     """At most 128 keys shared by at least 512 queries (the text cross-attention shape): keys
     and values stay in LDS, every key-group count 1..4, ragged query ranges and chunks."""
-    got, want = _attn_case(fc, G, nq, nk, d, gain, True, 0, scaled_q_rounding=True)
-    assert np.all(np.isfinite(got))
-    assert rel_l2(got, want) < 4e-3, (rel_l2(got, want), max_abs(got, want))
-    assert max_abs(got, want) < 2.5e-2
+    _check_flash(*_attn_case(fc, G, nq, nk, d, gain, True, 0, scaled_q_rounding=True), gain)
 
 
 @pytest.mark.parametrize("G,nq,nk,d,bf", [(2, 50, 70, 16, False), (3, 16, 16, 72, True), (1, 100, 130, 64, True),

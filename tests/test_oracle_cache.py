@@ -166,6 +166,21 @@ def test_a_step_that_is_a_multiple_of_the_base_is_restored_exactly():
     assert np.allclose(rec[0], first_s) and np.allclose(rec[1:], keys_s)
 
 
+def test_alpha_of_a_base_without_motion_is_zero():
+    """Common key frames equal to the first frame of the base step: Diff_base = 0, Eq. 2 is 0/0.
+    Every alpha then restores the same frames (first + alpha * 0), lstsq's minimum-norm answer is
+    0, and the result must be finite."""
+    rng = np.random.default_rng(12)
+    first_s = rng.standard_normal((3, 3, 2))
+    keys_s = rng.standard_normal((2, 3, 3, 2))
+    diff_base = np.zeros((2, 3, 3, 2))
+    a = cache.alpha_least_squares(first_s, keys_s, diff_base)
+    ref = np.linalg.lstsq(diff_base.reshape(-1, 1), (keys_s - first_s[None]).reshape(-1), rcond=None)[0][0]
+    assert a == 0.0 and ref == 0.0
+    rec = cache.decompress(first_s, diff_base, a, None, [0, 1, 2])
+    assert np.array_equal(rec, np.stack([first_s] * 3))
+
+
 def test_decompress_source_codes():
     rng = np.random.default_rng(11)
     first = rng.standard_normal((3, 3, 2))

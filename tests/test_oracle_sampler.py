@@ -257,6 +257,41 @@ def test_stochastic_ddim_special_cases():
     assert np.allclose(got, math.sqrt(a_p) * x0 + math.sqrt(1 - a_p - s * s) * e_true + s * z)
 
 
+def test_eta_one_is_the_ancestral_step_in_posterior_mean_form():
+    """Independent statement of the same step: at eta = 1 the DDIM family's member is the
+    ancestral sampler of the discrete diffusion between the two visited timesteps,
+      x_prev = (x_t - beta/sqrt(1-abar_t) eps) / sqrt(alpha) + sqrt(beta~) z,
+      alpha = abar_t/abar_prev, beta = 1 - alpha, beta~ = beta (1-abar_prev)/(1-abar_t),
+    written from the posterior q(x_prev | x_t, x0) and not through ddim_sigma.  A swapped
+    ratio or a wrong sign in the oracle's sigma or in its eps coefficient breaks it.  For
+    0 < eta < 1 the noise scale is eta times that one and the mean keeps variance
+    1 - abar_prev - sigma^2 on the eps direction, checked by Monte Carlo on the marginal."""
+    sched = synth.Schedule()
+    rng = np.random.default_rng(3)
+    x, eps, z = rng.standard_normal((5, 7)), rng.standard_normal((5, 7)), rng.standard_normal((5, 7))
+    for step in (1, 20, 37, 49):
+        _, a_t, a_p = sampler.step_coefficients(sched, step)
+        alpha = a_t / a_p
+        beta = 1.0 - alpha
+        post_var = beta * (1.0 - a_p) / (1.0 - a_t)
+        want = (x - beta / math.sqrt(1.0 - a_t) * eps) / math.sqrt(alpha) + math.sqrt(post_var) * z
+        got = sampler.ddim_update_stochastic(x, eps, a_t, a_p, 1.0, z)
+        assert np.allclose(got, want, rtol=1e-10, atol=1e-12), step
+        assert math.isclose(sampler.ddim_sigma(a_t, a_p, 0.5), 0.5 * math.sqrt(post_var), rel_tol=1e-12)
+    # marginal at an intermediate eta: from x_t ~ q(x_t | x0) with the true eps, x_prev ~ q(x_prev | x0),
+    # i.e. (x_prev - sqrt(abar_prev) x0) has variance 1 - abar_prev whatever eta is
+    _, a_t, a_p = sampler.step_coefficients(sched, 30)
+    n = 400_000
+    e_true, zz = rng.standard_normal(n), rng.standard_normal(n)
+    x0 = 0.3
+    xt = math.sqrt(a_t) * x0 + math.sqrt(1 - a_t) * e_true
+    for eta in (0.4, 1.0):
+        xp = sampler.ddim_update_stochastic(xt, e_true, a_t, a_p, eta, zz)
+        r = xp - math.sqrt(a_p) * x0
+        assert abs(r.mean()) < 4 * math.sqrt((1 - a_p) / n)
+        assert abs(r.var() / (1 - a_p) - 1.0) < 0.01
+
+
 def test_stochastic_step_uses_the_counter_noise_per_request():
     from dataclasses import replace
     sched = replace(synth.Schedule(num_steps=10), eta=0.5, seed=99)

@@ -34,6 +34,22 @@ def host(t):
     return t.detach().to(torch.float32).cpu().numpy()
 
 
+_WEIGHTS = []          # the most recent seeded weight sets: drawing a 28-block stack takes half a minute
+
+
+def cached_weights(cfg, seed, std=0.02):
+    """synth.make_weights, remembered for the tests that use the same model one after another."""
+    from paper_2501_04012_amd import synth
+    key = (cfg, seed, std)
+    for k, W in _WEIGHTS:
+        if k == key:
+            return W
+    W = synth.make_weights(cfg, seed, std=std)
+    _WEIGHTS.append((key, W))
+    del _WEIGHTS[:-2]
+    return W
+
+
 def run_step_gpu(fc, w, step=None, depth=None, weights=None, inputs=None, return_eps=True):
     """One fc_denoise_step of workload w on the GPU; returns (latent_after, eps)."""
     import torch
