@@ -265,8 +265,11 @@ int fc_op_linear(int32_t dtype, const void* A, const void* Wt, const float* bias
 /* Unmasked softmax(q k^T / sqrt(d)) v for G independent problems (one per
  * sequence and head).  q [G, nq, d], k [G, nk, d], v [G, nk, d], out [G, nq, d]
  * (all act).  impl 0: library's choice, 1: force the plain (non-MFMA) kernel.
- * The MFMA flash kernel works on bf16(q * log2(e)/sqrt(d)): inside a step the QKV
- * epilogue produces that from fp32; this stand-alone entry rounds its bf16 q again. */
+ * The MFMA kernels multiply bf16(q * log2(e)/sqrt(d)): inside a step the QKV epilogue
+ * produces that from fp32 with one rounding; with impl 0 this stand-alone entry has to
+ * round its bf16 q a second time.  impl 2: library's choice of kernel, and q is taken to
+ * hold q' = q * log2(e)/sqrt(d) already, i.e. out = softmax_2(q' k^T) v with
+ * softmax_2 the softmax to base 2: exactly what a step runs. */
 int fc_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* out,
                     int32_t G, int32_t nq, int32_t nk, int32_t d, int32_t impl, void* hip_stream);
 

@@ -814,8 +814,10 @@ int fc_op_attention(int32_t dtype, const void* q, const void* k, const void* v, 
   ap.groups = 1; ap.nq = nq; ap.nk = nk;
   ap.q_tokens = nq; ap.q_gstride = 0; ap.q_istride = 1;
   ap.k_tokens = nk; ap.k_gstride = 0; ap.k_istride = 1;
-  ap.scale_log2 = (float)(1.4426950408889634 / std::sqrt((double)d));
-  hipError_t e = launch_attention(dtype == FC_BF16, ap, impl, (hipStream_t)stream);
+  if (impl < 0 || impl > 2) return fail(FC_ERR_RANGE, "impl must be 0, 1 or 2");
+  // impl 2: q already carries the factor, as the QKV epilogue of a step leaves it
+  ap.scale_log2 = impl == 2 ? 1.0f : (float)(1.4426950408889634 / std::sqrt((double)d));
+  hipError_t e = launch_attention(dtype == FC_BF16, ap, impl == 2 ? 0 : impl, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return fail(FC_ERR_UNSUPPORTED, "head dim not supported or pointers not 16-byte aligned");
   HIP_TRY(e);
   return FC_OK;

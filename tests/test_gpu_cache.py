@@ -116,6 +116,21 @@ def test_alpha_against_oracle_and_repeatable(fc, n_base, H, W, C):
     record(alpha_rel_err=abs(float(a1) - want) / abs(want))
 
 
+def test_alpha_of_a_motionless_base_is_zero(fc):
+    """Diff_base = 0 (the common key frames repeat the first frame): Eq. 2 is 0/0; both sides
+    define alpha = 0 and nothing non-finite reaches the latent."""
+    torch = _torch()
+    rng = np.random.default_rng(3)
+    first = rng.standard_normal((8, 8, 4)).astype(np.float32)
+    keys = rng.standard_normal((2, 8, 8, 4)).astype(np.float32)
+    diff = np.zeros((2, 8, 8, 4), dtype=np.float32)
+    ws = torch.empty(fc.fc_cache_workspace_bytes(0), dtype=torch.uint8, device="cuda:0")
+    a = torch.full((1,), float("nan"), device="cuda:0")
+    fc.fc_cache_alpha(dev(first), dev(keys), dev(diff), 2, 8 * 8 * 4, a, ws)
+    torch.cuda.synchronize()
+    assert float(a) == ocache.alpha_least_squares(first, keys, diff) == 0.0
+
+
 @pytest.mark.parametrize("T,H,W,C", [(1, 4, 4, 4), (16, 32, 32, 4), (64, 40, 64, 4), (13, 60, 90, 16)])
 def test_frame_similarity_and_key_frames(fc, T, H, W, C):
     torch = _torch()
