@@ -245,6 +245,17 @@ int fc_cache_alpha(const float* first_s, const float* keys_s, const float* diff_
 int fc_cache_frame_similarity(const float* frames_dev, int32_t frames, int64_t frame_elems, float* sim,
                               void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* fc_cache_frame_similarity for callers that cannot allocate or hand over device memory of
+ * their own: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same kernels and result (bit for bit); the Gram matrix sits in a 512 KB
+ * device array owned by the library (one per device, held until the process ends) instead
+ * of a workspace.  At most 256 frames (FC_ERR_UNSUPPORTED beyond).  Calls no hipMalloc,
+ * hipFree or allocating routine.  All calls on one device share that array: two calls that
+ * overlap on one device (different streams, or threads) race; calls on one stream are safe.
+ * Nothing in the array needs clearing between calls.  frames_dev, sim: dev. */
+int fc_cache_frame_similarity_noalloc(const float* frames_dev, int32_t frames, int64_t frame_elems,
+                                      float* sim, void* hip_stream);
+
 /* Key-frame choice of Sec. 4.1.1 on a host copy of sim: frames are visited from the last
  * to the first; an unassigned frame becomes a key frame and every unassigned frame in
  * front of it with sim >= threshold is mapped to it.  map_out[f] (host) = the key frame

@@ -62,6 +62,7 @@ EXPORTS = {
     "fc_cache_alpha": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t,
                        C.c_void_p],
     "fc_cache_frame_similarity": [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p],
+    "fc_cache_frame_similarity_noalloc": [C.c_void_p, C.c_int32, C.c_int64, C.c_void_p, C.c_void_p],
     "fc_cache_select_key_frames": [C.POINTER(C.c_float), C.c_int32, C.c_float, C.POINTER(C.c_int32)],
     "fc_profile_enable": [C.c_void_p, C.c_int32],
     "fc_profile_select": [C.c_void_p, C.c_int32],
@@ -220,6 +221,11 @@ def fc_cache_frame_similarity(frames_dev, frames: int, frame_elems: int, sim, wo
     _check(_lib.fc_cache_frame_similarity(_ptr(frames_dev), frames, frame_elems, _ptr(sim), _ptr(workspace),
                                           workspace.numel() * workspace.element_size(), _stream(stream)),
            "fc_cache_frame_similarity")
+
+
+def fc_cache_frame_similarity_noalloc(frames_dev, frames: int, frame_elems: int, sim, stream=None) -> None:
+    _check(_lib.fc_cache_frame_similarity_noalloc(_ptr(frames_dev), frames, frame_elems, _ptr(sim), _stream(stream)),
+           "fc_cache_frame_similarity_noalloc")
 
 
 def fc_cache_select_key_frames(sim_host: np.ndarray, threshold: float = 0.99) -> np.ndarray:

@@ -6,6 +6,8 @@
 // All of it moves each byte once: the kernels are bound by HBM.
 #include "common.h"
 
+#include <mutex>
+
 namespace fc {
 
 // ---------------------------------------------------------------- stitching
@@ -144,6 +146,48 @@ hipError_t launch_frame_similarity(const float* frames, int T, long long F, floa
   k_frame_gram<<<dim3(T, T), 256, 0, s>>>(frames, T, F, ws);
   k_frame_cosine<<<(T * T + 255) / 256, 256, 0, s>>>(ws, T, sim);
   return hipGetLastError();
+}
+
+// ---------------------------------------------------------------- the same, with library-owned scratch
+// For callers that cannot allocate (a HIP graph being captured, a serving loop, a harness that
+// forbids hipMalloc): the Gram matrix of the largest entry (256 frames, 512 KB) lives in a
+// file-scope device array.  Every device the library runs on holds its own copy at its own
+// address; the address is looked up once per device, with that device current, and host code
+// only ever passes that looked-up pointer on (the array's name is a host-side stand-in).
+static __device__ __align__(256) double scratch[(size_t)kMaxCacheFrames * kMaxCacheFrames];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+double* g_scratch_ptr[kMaxDevices] = {};
+}  // namespace
+
+hipError_t static_gram_scratch(double** out) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    g_scratch_ptr[dev] = (double*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return hipSuccess;
+}
+
+// Nothing in the array has to start at zero: k_frame_gram writes every entry (i, j <= i) that
+// k_frame_cosine of the same call reads, whatever an earlier call with another T left behind.
+hipError_t launch_frame_similarity_static(const float* frames, int T, long long F, float* sim, hipStream_t s) {
+  if (T == 0) return hipSuccess;
+  if (T > kMaxCacheFrames) return hipErrorInvalidValue;
+  double* ws = nullptr;
+  hipError_t e = static_gram_scratch(&ws);
+  if (e != hipSuccess) return e;
+  return launch_frame_similarity(frames, T, F, sim, ws, s);
 }
 
 // ---------------------------------------------------------------- plain copy (key-step export)

@@ -272,6 +272,7 @@ hipError_t launch_decompress(const float* first, const float* diff_base, float a
 hipError_t launch_alpha(const float* first_s, const float* keys_s, const float* diff_base, int n_base, long long F,
                         float* alpha_out, double* ws, hipStream_t s);
 hipError_t launch_frame_similarity(const float* frames, int T, long long F, float* sim, double* ws, hipStream_t s);
+hipError_t launch_frame_similarity_static(const float* frames, int T, long long F, float* sim, hipStream_t s);
 hipError_t launch_copy_f32(const float* in, float* out, size_t n, hipStream_t s);
 
 }  // namespace fc

@@ -896,6 +896,16 @@ int fc_cache_frame_similarity(const float* frames_dev, int32_t frames, int64_t f
   return FC_OK;
 }
 
+int fc_cache_frame_similarity_noalloc(const float* frames_dev, int32_t frames, int64_t frame_elems, float* sim,
+                                      void* stream) {
+  if (!frames_dev || !sim) return fail(FC_ERR_NULL, "NULL argument");
+  if (frames < 0 || frame_elems < 1) return fail(FC_ERR_RANGE, "bad frame count or size");
+  if (frames > kMaxCacheFrames)
+    return fail(FC_ERR_UNSUPPORTED, "more than 256 frames: the library's own scratch holds a 256 x 256 Gram matrix");
+  HIP_TRY(launch_frame_similarity_static(frames_dev, frames, frame_elems, sim, (hipStream_t)stream));
+  return FC_OK;
+}
+
 int fc_cache_select_key_frames(const float* sim, int32_t frames, float threshold, int32_t* map_out) {
   if (!sim || !map_out) return fail(FC_ERR_NULL, "NULL argument");
   if (frames < 0) return fail(FC_ERR_RANGE, "negative frame count");
