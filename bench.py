@@ -220,6 +220,94 @@ def hbm_ops_bench(args):
         "ops": out}))
 
 
+def mfma_ceiling_bench(args):
+    """Secondary measurement (--mfma-ceiling): what the part at hand sustains.
+    (1) The library's pipe-rate microbenchmark: independent bf16 32x32x16 MFMA chains on random
+    and on constant operands, v_exp_f32 streams, both in one wave, and MFMA waves beside
+    exponential waves on the same SIMDs, each with the shader clock it ran at.
+    (2) Yardsticks, not on the product path: torch.matmul (bf16, the vendor's GEMM library) on
+    the four GEMM shapes of the full-3D configuration and torch's fused attention on its
+    attention shape, timed on the same box.  One JSON line."""
+    import torch
+    import paper_2501_04012_amd as fc
+    torch.cuda.set_device(0)
+    g = torch.Generator(device="cuda").manual_seed(1)
+
+    def timed(fn, reps):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    rnd = torch.randn(4096, device="cuda", generator=g).to(torch.bfloat16)
+    const = torch.ones(4096, device="cuda", dtype=torch.bfloat16)
+    iters = 200000
+    pipes = {}
+    for label, ops, ma, mb, blocks in (
+            ("mfma_random_operands_2_waves_per_simd", rnd, 1, 1, 256),
+            ("mfma_random_operands_4_waves_per_simd", rnd, 1, 1, 512),
+            ("mfma_constant_operands_2_waves_per_simd", const, 1, 1, 256),
+            ("exp_only_2_waves_per_simd", rnd, 2, 2, 256),
+            ("mfma_and_exp_in_one_wave", rnd, 3, 3, 256),
+            ("mfma_waves_beside_exp_waves", rnd, 1, 2, 256)):
+        sink = torch.empty(blocks * 512, device="cuda")
+        clocks = torch.zeros(blocks * 16, dtype=torch.int64, device="cuda")
+        ms = timed(lambda: fc.fc_bench_pipe_rates(ops, iters, ma, mb, blocks, sink, clocks), 3)
+        c = clocks.cpu().numpy().reshape(-1, 2).astype(np.float64)
+        mfma_waves = blocks * (4 * (ma & 1) + 4 * (mb & 1))
+        exp_waves = blocks * (4 * ((ma >> 1) & 1) + 4 * ((mb >> 1) & 1))
+        r = {"ms": ms, "shader_clock_ghz": float(np.median(c[:, 0] / np.maximum(c[:, 1], 1.0)) * 0.1)}
+        if mfma_waves:
+            r["mfma_tflops"] = mfma_waves * iters * 4 * 32768.0 / (ms * 1e-3) / 1e12
+        if exp_waves:
+            r["exp_per_ns"] = exp_waves * iters * 8 * 64.0 / (ms * 1e6)
+        if ma != mb:        # the two halves finish at different times: per-half durations from the wave clocks
+            half = c.reshape(blocks, 8, 2)
+            r["first_half_ms"] = float(np.median(half[:, :4, 1])) * 1e-5
+            r["second_half_ms"] = float(np.median(half[:, 4:, 1])) * 1e-5
+        pipes[label] = r
+
+    yard = {}
+    M = 17776
+    for name, K, N in (("qkv", 3072, 9216), ("proj", 3072, 3072), ("fc1", 3072, 12288), ("fc2", 12288, 3072)):
+        a = (torch.randn(M, K, device="cuda", generator=g)).to(torch.bfloat16)
+        wt = (0.02 * torch.randn(N, K, device="cuda", generator=g)).to(torch.bfloat16)
+        o = torch.empty(M, N, device="cuda", dtype=torch.bfloat16)
+        ms = timed(lambda: torch.matmul(a, wt.t(), out=o), 10)
+        yard["torch_matmul_" + name] = {"m_n_k": [M, N, K], "ms": ms, "tflops": 2.0 * M * N * K / (ms * 1e-3) / 1e12}
+        # the library's own linear on the same operands, same timing loop
+        ms = timed(lambda: fc.fc_op_linear(fc.FC_BF16, a, wt, None, None, o, M, N, K, 0), 10)
+        yard["fc_op_linear_" + name] = {"m_n_k": [M, N, K], "ms": ms, "tflops": 2.0 * M * N * K / (ms * 1e-3) / 1e12}
+        del a, wt, o
+    try:
+        H, Nt, d = 48, 17776, 64
+        q = torch.randn(1, H, Nt, d, device="cuda", generator=g).to(torch.bfloat16)
+        k = torch.randn(1, H, Nt, d, device="cuda", generator=g).to(torch.bfloat16)
+        v = torch.randn(1, H, Nt, d, device="cuda", generator=g).to(torch.bfloat16)
+        ms = timed(lambda: torch.nn.functional.scaled_dot_product_attention(q, k, v), 3)
+        yard["torch_sdpa_full3d"] = {"heads_tokens_d": [H, Nt, d], "ms": ms, "tflops": 4.0 * H * Nt * Nt * d / (ms * 1e-3) / 1e12}
+        o = torch.empty(H, Nt, d, device="cuda", dtype=torch.bfloat16)
+        ms = timed(lambda: fc.fc_op_attention(fc.FC_BF16, q[0], k[0], v[0], o, H, Nt, Nt, d, 0), 3)
+        yard["fc_op_attention_full3d"] = {"heads_tokens_d": [H, Nt, d], "ms": ms,
+                                          "tflops": 4.0 * H * Nt * Nt * d / (ms * 1e-3) / 1e12}
+    except Exception as exc:                      # the yardstick is optional: some builds carry no fused attention
+        yard["torch_sdpa_full3d"] = {"error": repr(exc)[:200]}
+    best = pipes["mfma_random_operands_2_waves_per_simd"]
+    print(json.dumps({
+        "metric": "sustained bf16 MFMA TFLOP/s of independent 32x32x16 chains on random operands", "value": best["mfma_tflops"],
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": 3, "warmup": 2, "ms_per_step": best["ms"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "mfma_ceiling"},
+        "roofline": {"kernel": "k_pipe_rates", "bound": "mfma", "achieved": best["mfma_tflops"], "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": best["mfma_tflops"] / PEAK_BF16_TFLOPS, "traffic": None},
+        "pipes": pipes, "yardsticks": yard}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -231,6 +319,8 @@ def main():
                     help="time the cache-restore entry points instead of a denoising workload")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this size (a known-size kernel for scaling HBM counters)")
+    ap.add_argument("--mfma-ceiling", action="store_true",
+                    help="microbenchmarks of the matrix / vector pipes and vendor-library yardsticks instead")
     ap.add_argument("--hbm-ops", action="store_true",
                     help="time LayerNorm+modulate and the guidance+DDIM update at real and scaled shapes instead")
     args = ap.parse_args()
@@ -251,6 +341,9 @@ def main():
         return
     if args.hbm_ops:
         hbm_ops_bench(args)
+        return
+    if args.mfma_ceiling:
+        mfma_ceiling_bench(args)
         return
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]

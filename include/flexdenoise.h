@@ -308,6 +308,20 @@ int fc_op_patch_embed(const float* latent, int32_t R, int32_t B, const float* Wp
 int fc_op_cfg_ddim(float* x, const float* eps_c, const float* eps_u, float* eps_out, size_t n_total,
                    float guidance_scale, const float* coef4_host, void* hip_stream);
 
+/* ---- measurement aid, not part of a step: the rates of a compute unit's matrix pipe and
+ * vector pipe under the instruction mix of the attention kernel (bf16 32x32x16 MFMAs, two
+ * v_exp_f32 per MFMA), on the part at hand and at the clock it sustains under that load.
+ * `blocks` workgroups of 8 waves run `iters` iterations; the first four waves of a workgroup
+ * run mode_first, the last four mode_second: 0 idle, 1 four independent MFMA chains per
+ * iteration (4 * 32768 FLOP per wave and iteration), 2 eight exponentials per iteration,
+ * 3 both interleaved in one instruction stream.  operands: dev, 4096 bf16 (16-byte aligned)
+ * that fill the MFMA inputs (random values load the pipe like real data, constants do not);
+ * sink: dev, blocks * 512 floats (keeps the work alive); clocks: dev, blocks * 8 pairs of
+ * int64: per wave the loop's duration in shader-clock cycles and on the 100 MHz constant
+ * counter (their ratio is the sustained shader clock). */
+int fc_bench_pipe_rates(const void* operands, int32_t iters, int32_t mode_first, int32_t mode_second,
+                        int32_t blocks, float* sink, int64_t* clocks, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -77,6 +77,7 @@ EXPORTS = {
     "fc_op_patch_embed": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                           C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                           C.c_int32, C.c_void_p],
+    "fc_bench_pipe_rates": [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p],
     "fc_op_cfg_ddim": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_float,
                        C.POINTER(C.c_float), C.c_void_p],
 }
@@ -226,6 +227,12 @@ def fc_cache_frame_similarity(frames_dev, frames: int, frame_elems: int, sim, wo
 def fc_cache_frame_similarity_noalloc(frames_dev, frames: int, frame_elems: int, sim, stream=None) -> None:
     _check(_lib.fc_cache_frame_similarity_noalloc(_ptr(frames_dev), frames, frame_elems, _ptr(sim), _stream(stream)),
            "fc_cache_frame_similarity_noalloc")
+
+
+def fc_bench_pipe_rates(operands, iters: int, mode_first: int, mode_second: int, blocks: int, sink, clocks,
+                        stream=None) -> None:
+    _check(_lib.fc_bench_pipe_rates(_ptr(operands), iters, mode_first, mode_second, blocks, _ptr(sink), _ptr(clocks),
+                                    _stream(stream)), "fc_bench_pipe_rates")
 
 
 def fc_cache_select_key_frames(sim_host: np.ndarray, threshold: float = 0.99) -> np.ndarray:

@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libflexdenoise.so")
-SOURCES = ["flexdenoise.hip", "elementwise.hip", "gemm.hip", "attention.hip", "cache.hip"]
+SOURCES = ["flexdenoise.hip", "elementwise.hip", "gemm.hip", "attention.hip", "cache.hip", "microbench.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -41,7 +41,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
             return o, ""
         return o, _run([HIPCC, *FLAGS, "-c", s, "-o", o])
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         results = list(ex.map(compile_one, SOURCES))
     for _, log in results:
         if verbose and log.strip():

@@ -273,6 +273,8 @@ hipError_t launch_alpha(const float* first_s, const float* keys_s, const float* 
                         float* alpha_out, double* ws, hipStream_t s);
 hipError_t launch_frame_similarity(const float* frames, int T, long long F, float* sim, double* ws, hipStream_t s);
 hipError_t launch_frame_similarity_static(const float* frames, int T, long long F, float* sim, hipStream_t s);
+hipError_t launch_pipe_rates(const void* operands, int iters, int mode_a, int mode_b, int blocks, float* sink,
+                             long long* clocks, hipStream_t s);
 hipError_t launch_copy_f32(const float* in, float* out, size_t n, hipStream_t s);
 
 }  // namespace fc

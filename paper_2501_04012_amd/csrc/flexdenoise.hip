@@ -921,6 +921,18 @@ int fc_cache_select_key_frames(const float* sim, int32_t frames, float threshold
   return FC_OK;
 }
 
+int fc_bench_pipe_rates(const void* operands, int32_t iters, int32_t mode_first, int32_t mode_second, int32_t blocks,
+                        float* sink, int64_t* clocks, void* stream) {
+  if (!operands || !sink || !clocks) return fail(FC_ERR_NULL, "NULL argument");
+  if (iters < 1 || iters > (1 << 24) || blocks < 1 || blocks > 65536 || mode_first < 0 || mode_first > 3 ||
+      mode_second < 0 || mode_second > 3)
+    return fail(FC_ERR_RANGE, "iters in 1..2^24, blocks in 1..65536, modes in 0..3");
+  if (((uintptr_t)operands & 15) != 0) return fail(FC_ERR_RANGE, "operands must be 16-byte aligned");
+  HIP_TRY(launch_pipe_rates(operands, iters, mode_first, mode_second, blocks, sink, (long long*)clocks,
+                            (hipStream_t)stream));
+  return FC_OK;
+}
+
 int fc_op_cfg_ddim(float* x, const float* eps_c, const float* eps_u, float* eps_out, size_t n, float gs,
                    const float* coef4, void* stream) {
   if (!x || !eps_c || !coef4) return fail(FC_ERR_NULL, "NULL argument");
