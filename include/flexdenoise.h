@@ -284,6 +284,15 @@ int fc_op_linear(int32_t dtype, const void* A, const void* Wt, const float* bias
 int fc_op_attention(int32_t dtype, const void* q, const void* k, const void* v, void* out,
                     int32_t G, int32_t nq, int32_t nk, int32_t d, int32_t impl, void* hip_stream);
 
+/* The attention of a long sequence as a step runs it (bf16, head dim 64 or 72): q holds
+ * q' = q * log2(e)/sqrt(d) as in impl 2 above, and the keys' largest Euclidean norm per problem
+ * is computed first (into key_norm_scratch: dev, 32 * G floats, overwritten), which bounds
+ * every score by |q'| max|k| and lets the kernel drop the running maximum where that bound
+ * is close enough to the first tile's maximum (otherwise it keeps it: same result up to
+ * rounding).  Key sequences too short to profit run the same kernels as fc_op_attention. */
+int fc_op_attention_bounded(const void* q, const void* k, const void* v, void* out, int32_t G, int32_t nq,
+                            int32_t nk, int32_t d, float* key_norm_scratch, void* hip_stream);
+
 /* If y (act, [M,D]) is not NULL: x[M,D] (f32) <- x + y first (the pending branch output).
  * Then out[M,D] (act) = LayerNorm(x) * (1 + scale[D]) + shift[D] (shift/scale f32, both
  * NULL = plain LayerNorm); D a multiple of 4, at most 4096. */

@@ -72,6 +72,8 @@ EXPORTS = {
                      C.c_int32, C.c_int32, C.c_void_p],
     "fc_op_attention": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                         C.c_int32, C.c_int32, C.c_void_p],
+    "fc_op_attention_bounded": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                C.c_int32, C.c_void_p, C.c_void_p],
     "fc_op_layernorm_modulate": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                  C.c_int32, C.c_float, C.c_void_p],
     "fc_op_patch_embed": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -291,6 +293,11 @@ def fc_op_linear(dtype, A, Wt, bias, gate, out, M, N, K, epilogue, stream=None) 
 def fc_op_attention(dtype, q, k, v, out, G, nq, nk, d, impl=0, stream=None) -> None:
     _check(_lib.fc_op_attention(dtype, _ptr(q), _ptr(k), _ptr(v), _ptr(out), G, nq, nk, d, impl, _stream(stream)),
            "fc_op_attention")
+
+
+def fc_op_attention_bounded(q, k, v, out, G, nq, nk, d, key_norm_scratch, stream=None) -> None:
+    _check(_lib.fc_op_attention_bounded(_ptr(q), _ptr(k), _ptr(v), _ptr(out), G, nq, nk, d, _ptr(key_norm_scratch),
+                                        _stream(stream)), "fc_op_attention_bounded")
 
 
 def fc_op_layernorm_modulate(dtype, x, y, shift, scale, out, M, D, eps, stream=None) -> None:

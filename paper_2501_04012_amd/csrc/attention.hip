@@ -444,6 +444,15 @@ static hipError_t dispatch_plain(const AttnParams& p, bool allow_short, hipStrea
 //
 // HD = true head dim; HDP = HD rounded up to 16 (contraction of Q K^T); HDV = HD
 // rounded up to 32 (rows of O^T).  Pad lanes are zero-filled when staged.
+//
+// Bounded form (p.key_norm_max given).  The running reference only has to keep exp2(s - m)
+// inside the floating-point range, and a score cannot exceed |q_i| max_j |k_j| in magnitude
+// (Cauchy-Schwarz).  A wave whose query columns all satisfy |q_i| max|k| <= kBoundSlack can
+// therefore keep the reference m = 0 for the whole key sequence: no maximum, no comparison,
+// no reference update on any tile, and the vector work per score drops to exp2, packing and
+// the row sum (a quarter of the vector instructions, and the cross-lane exchange with its
+// wait, leave the loop).  Waves that do not satisfy it (large logits: peaked rows) run the
+// lazy-maximum loop; the choice is wave-uniform.  Same softmax either way, another reference.
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 template <int HD>
@@ -515,6 +524,28 @@ __global__ __launch_bounds__(64 * NWV, ((HD <= 64 || QT == 1) ? 2 : 1)) void k_a
       }
       qf[qt][s] = v;
     }
+  }
+
+  // ---- bounded form: is |q_i| max_j |k_j| (with a margin for the rounding of the norms) within
+  //      the slack for every query column of this wave?  2^kBoundSlack times the number of
+  //      keys times |v| stays far inside fp32, and so does 2^-kBoundSlack.
+  constexpr float kBoundSlack = 40.0f;
+  bool fast = false;
+  if (p.key_norm_max != nullptr) {
+    const float* kn = p.key_norm_max + ((size_t)kb * p.heads + head) * kKeyNormChunks;
+    const float kmax = wave_max(kn[lane & (kKeyNormChunks - 1)]);
+    float worst = 0.0f;
+#pragma unroll
+    for (int qt = 0; qt < QT; ++qt) {
+      float ss = 0.0f;
+#pragma unroll
+      for (int s = 0; s < C::KS; ++s)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss = __builtin_fmaf((float)qf[qt][s][e], (float)qf[qt][s][e], ss);
+      worst = fmaxf(worst, ss);
+    }
+    worst += __shfl_xor(worst, 32, 64);        // at least the larger column's squared norm: a safe over-estimate
+    fast = !__any(!(__builtin_sqrtf(worst) * kmax * 1.001f + 0.01f <= kBoundSlack));
   }
 
   f32x16 oacc[C::CT][QT];
@@ -596,9 +627,10 @@ __global__ __launch_bounds__(64 * NWV, ((HD <= 64 || QT == 1) ? 2 : 1)) void k_a
   ones[0] = (bf16_t)1.0f; ones[1] = (bf16_t)1.0f;
   constexpr float kLazy = 8.0f;
 
-  // One key tile.  MASKED: the tile holds keys past nk (only the last tile can).
-  auto tile = [&](int kt, auto masked_tag) {
-    constexpr bool MASKED = decltype(masked_tag)::value;
+  // One key tile.  MASKED: the tile holds keys past nk (only the last tile can).  NOMAX: the
+  // reference is known to bound every score closely enough (bounded form): no maximum.
+  auto tile = [&](int kt, auto masked_tag, auto nomax_tag) {
+    constexpr bool MASKED = decltype(masked_tag)::value, NOMAX = decltype(nomax_tag)::value;
     const int buf = kt & 1;
     if (kt + 1 < nkt) gload(kt + 1);
     const bf16_t* ks = Ks + buf * C::K_ELEMS;
@@ -640,6 +672,7 @@ __global__ __launch_bounds__(64 * NWV, ((HD <= 64 || QT == 1) ? 2 : 1)) void k_a
     //      kLazy are let through (p <= 2^kLazy, harmless in fp32/bf16); only when a column
     //      exceeds it, or on the first tile, is m moved and O, l, S rescaled.  The branch is
     //      wave-uniform and rare after the first tiles.
+    if constexpr (!NOMAX) {
     float mx[QT];
 #pragma unroll
     for (int qt = 0; qt < QT; ++qt) {
@@ -672,6 +705,7 @@ __global__ __launch_bounds__(64 * NWV, ((HD <= 64 || QT == 1) ? 2 : 1)) void k_a
 #pragma unroll
         for (int r = 0; r < 16; ++r) negm[qt][r] -= delta;
       }
+    }
     }
 
     // ---- P = exp2(S), packed to bf16 in B-operand order; the row sum adds the rounded
@@ -724,8 +758,14 @@ __global__ __launch_bounds__(64 * NWV, ((HD <= 64 || QT == 1) ? 2 : 1)) void k_a
   };
 
   const int nfull = p.nk / 64;
-  for (int kt = 0; kt < nfull; ++kt) tile(kt, std::false_type{});
-  if (nfull < nkt) tile(nfull, std::true_type{});
+  using T_ = std::true_type; using F_ = std::false_type;
+  if (fast) {
+    for (int kt = 0; kt < nfull; ++kt) tile(kt, F_{}, T_{});
+    if (nfull < nkt) tile(nfull, T_{}, T_{});
+  } else {
+    for (int kt = 0; kt < nfull; ++kt) tile(kt, F_{}, F_{});
+    if (nfull < nkt) tile(nfull, T_{}, F_{});
+  }
 
   // ---- finish: O / l, write token-major.  Lane (i, h) holds query column i, head
   //      dims 32c + 8g + 4h + e in register 4g + e.
@@ -994,6 +1034,65 @@ static bool flash_ok(const AttnParams& p) {
   if (p.nk < 1 || p.nq < 1) return false;
   if ((((uintptr_t)p.q | (uintptr_t)p.k | (uintptr_t)p.v | (uintptr_t)p.out) & 15) != 0) return false;
   return true;
+}
+
+// ---------------------------------------------------------------- largest key norm per (key batch, head)
+// Partial maxima over kKeyNormChunks ranges of the key rows; the flash kernel takes their
+// maximum.  Eight lanes share a row of 64 elements (one 16-byte load each, coalesced), else
+// one thread per row.  A maximum is order-independent: the result is bitwise repeatable.
+template <int HD>
+__global__ __launch_bounds__(256) void k_key_norm_max(const bf16_t* __restrict__ k, int k_tokens, float* __restrict__ out) {
+  __shared__ float sh[4];
+  const int chunk = blockIdx.x, bh = blockIdx.y;
+  const int per = (k_tokens + kKeyNormChunks - 1) / kKeyNormChunks;
+  const int r0 = chunk * per, r1 = min(k_tokens, r0 + per);
+  const bf16_t* base = k + (size_t)bh * k_tokens * HD;
+  float best = 0.0f;
+  if constexpr (HD == 64) {
+    const int sub = threadIdx.x & 7;
+    for (int r = r0 + (threadIdx.x >> 3); r < r1; r += 32) {
+      const bf16x8 v = *(const bf16x8*)(base + (size_t)r * HD + sub * 8);
+      float ss = 0.0f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) ss = __builtin_fmaf((float)v[e], (float)v[e], ss);
+      ss += __shfl_xor(ss, 1, 64);
+      ss += __shfl_xor(ss, 2, 64);
+      ss += __shfl_xor(ss, 4, 64);
+      best = fmaxf(best, ss);
+    }
+  } else {
+    for (int r = r0 + threadIdx.x; r < r1; r += 256) {
+      float ss = 0.0f;
+#pragma unroll
+      for (int c = 0; c < HD / 8; ++c) {
+        const bf16x8 v = *(const bf16x8*)(base + (size_t)r * HD + c * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ss = __builtin_fmaf((float)v[e], (float)v[e], ss);
+      }
+      best = fmaxf(best, ss);
+    }
+  }
+  best = wave_max(best);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = best;
+  __syncthreads();
+  if (threadIdx.x == 0)
+    out[(size_t)bh * kKeyNormChunks + chunk] = __builtin_sqrtf(fmaxf(fmaxf(sh[0], sh[1]), fmaxf(sh[2], sh[3])));
+}
+
+hipError_t launch_key_norm_max(const void* k, int KB, int heads, int k_tokens, int hd, float* out, hipStream_t s) {
+  if ((long long)KB * heads == 0) return hipSuccess;
+  if (k_tokens < 1 || (long long)KB * heads > 65535 || (((uintptr_t)k) & 15) != 0) return hipErrorInvalidValue;
+  dim3 grid(kKeyNormChunks, (unsigned)(KB * heads));
+  if (hd == 64) k_key_norm_max<64><<<grid, 256, 0, s>>>((const bf16_t*)k, k_tokens, out);
+  else if (hd == 72) k_key_norm_max<72><<<grid, 256, 0, s>>>((const bf16_t*)k, k_tokens, out);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+// The bound pays once there are many key tiles per query tile; the few-keys kernel and the
+// short-sequence kernels take no reference from it.
+bool attention_uses_key_norms(int bf16, const AttnParams& p) {
+  return bf16 && flash_ok(p) && !kvres_ok(p) && p.nk >= 2048 && p.groups == 1 && !p.kv_shared_tail;
 }
 
 hipError_t launch_attention(int bf16, const AttnParams& p, int impl, hipStream_t s) {

@@ -234,7 +234,12 @@ struct AttnParams {
   int k_tokens, k_gstride, k_istride;
   int kv_split, kv_shared_tail;
   float scale_log2;   // factor still to be applied to q.k: scale*log2(e), or 1 if q already carries it
+  // Optional (bf16 flash kernel, long key sequences): [KB, heads, kKeyNormChunks] partial maxima of
+  // the key rows' Euclidean norms, from launch_key_norm_max.  With them a query's scores are
+  // bounded by |q| max|k| and the kernel can drop the per-tile maximum (see k_attn_flash).
+  const float* key_norm_max;
 };
+constexpr int kKeyNormChunks = 32;
 
 // ---------------------------------------------------------------- launchers (defined in the .hip files)
 hipError_t launch_convert_f32(const float* in, void* out, size_t n, int to_bf16, hipStream_t s);
@@ -261,6 +266,11 @@ hipError_t launch_cfg_ddim_noise(float* x, const float* eps_c, const float* eps_
 hipError_t launch_gemm(int bf16, int mode, const void* A, const void* Wt, int M, int N, int K,
                        const EpiParams& ep, hipStream_t s);
 hipError_t launch_attention(int bf16, const AttnParams& p, int impl, hipStream_t s);
+// out [KB * heads * kKeyNormChunks] (f32): per (key batch, head) and chunk of the k_tokens rows of
+// k [KB, heads, k_tokens, hd] (bf16), the largest Euclidean row norm (0 for an empty chunk)
+hipError_t launch_key_norm_max(const void* k, int KB, int heads, int k_tokens, int hd, float* out, hipStream_t s);
+// true where launch_attention would make use of key_norm_max
+bool attention_uses_key_norms(int bf16, const AttnParams& p);
 
 // cache restore (cache.hip)
 constexpr int kMaxCacheFrames = 256;     // frames of one entry (source codes travel as a kernel argument)

@@ -243,6 +243,7 @@ struct Workspace {
   float* x;                                // residual stream fp32 [B, Ns, D]
   void *u, *q, *k, *v, *hid;               // activations
   float* eps;                              // [B, T, H, W, C]
+  float* knorm;                            // [B, heads, kKeyNormChunks] largest key norms (long-sequence attention)
   size_t bytes;
   int B, NT;
 };
@@ -273,6 +274,7 @@ Workspace carve(const fc_model* m, int R, int use_cfg, unsigned char* base) {
   w.v = cv.take(rows * D * es);
   w.hid = cv.take(rows * c.mlp_dim * es);
   w.eps = (float*)cv.take((size_t)w.B * c.frames * c.height * c.width * c.channels * 4);
+  w.knorm = (float*)cv.take((size_t)w.B * c.heads * kKeyNormChunks * 4);
   w.bytes = cv.off;
   return w;
 }
@@ -398,6 +400,12 @@ int self_attention_branch(const Ctx& c, const Linear& qkv, const Linear& proj, c
   ap.scale_log2 = 1.0f;                  // q was stored pre-scaled by the QKV epilogue
   {
     ProfScope ps(c, mode == 0 ? PC_ATTN_SPATIAL : mode == 1 ? PC_ATTN_TEMPORAL : PC_ATTN_FULL);
+    if (attention_uses_key_norms(m->bf16, ap)) {
+      // long sequences: the largest key norm per head bounds every score, which lets the
+      // attention kernel drop its per-tile maximum
+      HIP_TRY(launch_key_norm_max(w.k, w.B, cf.heads, m->Ns, m->hd, w.knorm, c.s));
+      ap.key_norm_max = w.knorm;
+    }
     HIP_TRY(launch_attention(m->bf16, ap, 0, c.s));
   }
   return branch_out(c, PC_GEMM_PROJ, w.u, proj, gate);
@@ -820,6 +828,26 @@ int fc_op_attention(int32_t dtype, const void* q, const void* k, const void* v, 
   hipError_t e = launch_attention(dtype == FC_BF16, ap, impl == 2 ? 0 : impl, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return fail(FC_ERR_UNSUPPORTED, "head dim not supported or pointers not 16-byte aligned");
   HIP_TRY(e);
+  return FC_OK;
+}
+
+int fc_op_attention_bounded(const void* q, const void* k, const void* v, void* out, int32_t G, int32_t nq, int32_t nk,
+                            int32_t d, float* key_norm_scratch, void* stream) {
+  if (!q || !k || !v || !out || !key_norm_scratch) return fail(FC_ERR_NULL, "NULL argument");
+  if (G < 0 || G > 65535 || nq < 0 || nk < 1) return fail(FC_ERR_RANGE, "bad size");
+  if (d != 64 && d != 72) return fail(FC_ERR_UNSUPPORTED, "head dim must be 64 or 72");
+  AttnParams ap{};
+  ap.q = q; ap.k = k; ap.v = v; ap.out = out;
+  ap.B = G; ap.heads = 1; ap.hd = d;
+  ap.groups = 1; ap.nq = nq; ap.nk = nk;
+  ap.q_tokens = nq; ap.q_gstride = 0; ap.q_istride = 1;
+  ap.k_tokens = nk; ap.k_gstride = 0; ap.k_istride = 1;
+  ap.scale_log2 = 1.0f;
+  if ((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) != 0)
+    return fail(FC_ERR_UNSUPPORTED, "pointers not 16-byte aligned");
+  HIP_TRY(launch_key_norm_max(k, G, 1, nk, d, key_norm_scratch, (hipStream_t)stream));
+  ap.key_norm_max = key_norm_scratch;
+  HIP_TRY(launch_attention(1, ap, 0, (hipStream_t)stream));
   return FC_OK;
 }
 

@@ -175,6 +175,39 @@ def test_attention_few_keys_many_queries_bf16(fc, G, nq, nk, d, gain):
     _check_flash_both_forms(fc, G, nq, nk, d, gain)
 
 
+@pytest.mark.parametrize("G,nq,nk,d", [(2, 4200, 2100, 64),      # 8-wave workgroups, ragged both ways
+                                       (3, 600, 2300, 64),       # 4-wave workgroups
+                                       (2, 700, 2048, 72),       # head dim 72, whole tiles
+                                       (1, 300, 333, 64)])       # too short to use the bound: plain path
+@pytest.mark.parametrize("gain", [0.5, 1.0, 2.5, 4.0])
+def test_attention_with_the_key_norm_bound(fc, G, nq, nk, d, gain):
+    """Long key sequences in the form a step runs them: scores bounded by |q| max|k|.  Small
+    gains keep every query column inside the slack (no running maximum after the first tile),
+    large gains do not (the lazy-maximum loop); gain 1 mixes both among the waves of a launch.
+    The result must meet the step's bar against the oracle on the same inputs either way, and
+    agree with the unbounded kernel to rounding."""
+    torch = _torch()
+    q, k, v = _attn_inputs(G, nq, nk, d, gain, True)
+    c = np.float32(1.4426950408889634 / math.sqrt(d))
+    q_pre = BF(q.astype(np.float32) * c)
+    want = dit.attention(q_pre.astype(np.float64) / np.float64(c), k.astype(np.float64), v.astype(np.float64))
+    out = torch.full((G, nq, d), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    scratch = torch.full((32 * G,), float("nan"), device="cuda:0")
+    fc.fc_op_attention_bounded(dev(q_pre, True), dev(k, True), dev(v, True), out, G, nq, nk, d, scratch)
+    torch.cuda.synchronize()
+    got = host(out)
+    assert np.all(np.isfinite(got))
+    record(gain=gain, rel_l2=rel_l2(got, want), max_abs=max_abs(got, want))
+    assert rel_l2(got, want) < 4e-3 and max_abs(got, want) < 2.5e-2, (rel_l2(got, want), max_abs(got, want))
+    # the scratch holds the largest key norm of each problem (maximum over its 32 partial maxima)
+    norms = host(scratch).reshape(G, 32).max(axis=1)
+    np.testing.assert_allclose(norms, np.linalg.norm(k.astype(np.float64), axis=2).max(axis=1), rtol=1e-5)
+    ref = torch.full((G, nq, d), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    fc.fc_op_attention(fc.FC_BF16, dev(q_pre, True), dev(k, True), dev(v, True), ref, G, nq, nk, d, 2)
+    torch.cuda.synchronize()
+    assert rel_l2(got, host(ref)) < 4e-3
+
+
 @pytest.mark.parametrize("G,nq,nk,d,bf", [(2, 50, 70, 16, False), (3, 16, 16, 72, True), (1, 100, 130, 64, True),
                                           (2, 9, 5, 8, False), (1, 20, 40, 128, False)])
 def test_attention_plain(fc, G, nq, nk, d, bf):
