@@ -25,11 +25,12 @@ PEAK_HBM_GBS = 8000.0
 
 
 def measured_traffic(kernel):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary, or None
-    when there is none or the kernel source has changed since the counters were taken."""
+    """(HBM bytes per launch of `kernel`, where the figure comes from): the bytes are replayed
+    from the committed rocprofv3 counter summary, not counted in this run; (None, reason) when
+    there is no summary or the kernel source has changed since the counters were taken."""
     import glob
     import hashlib
-    for path in glob.glob(os.path.join(ROOT, "profiles", "*hbm_traffic.txt")):
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*hbm_traffic.txt"))):
         kv = {}
         for line in open(path):
             if "=" in line and not line.startswith("#"):
@@ -38,10 +39,13 @@ def measured_traffic(kernel):
         if f"{kernel}.fetch_bytes" not in kv:
             continue
         src = os.path.join(ROOT, "paper_2501_04012_amd", "csrc", "attention.hip")
+        rel = os.path.relpath(path, ROOT)
         if hashlib.sha256(open(src, "rb").read()).hexdigest() != kv.get(f"{kernel}.source_sha256"):
-            return None
-        return float(kv[f"{kernel}.fetch_bytes"]) + float(kv[f"{kernel}.write_bytes"])
-    return None
+            return None, f"{rel}: stale (the kernel source changed after the counters were taken)"
+        return (float(kv[f"{kernel}.fetch_bytes"]) + float(kv[f"{kernel}.write_bytes"]),
+                f"replayed from {rel} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, taken {kv.get('date', 'date not recorded')}); "
+                f"not counted in this run")
+    return None, "no counter summary under profiles/"
 
 
 def cpu_baseline(w, weights, lat, cond):
@@ -57,20 +61,13 @@ def cpu_baseline(w, weights, lat, cond):
     cfg = w.model
     W32 = {k: np.asarray(v, dtype=np.float32) for k, v in weights.items()}
     if cfg.attn_mode == synth.ATTN_FULL3D_CONCAT and cfg.depth == 1:
-        # evaluate n1 and 2*n1 sampled query rows; the cost is affine in the row count
-        rng = np.random.default_rng(0)
-        n1 = 2048                                # about 10 s of host work in all
-        rows = rng.choice(cfg.video_tokens, size=2 * n1, replace=False)
-        t0 = time.perf_counter(); dit.forward(cfg, W32, lat[0], cond[0], 500, dtype=None, video_rows=rows[:n1])
-        t1 = time.perf_counter(); dit.forward(cfg, W32, lat[0], cond[0], 500, dtype=None, video_rows=rows)
-        t2 = time.perf_counter()
-        a, b = (t1 - t0), (t2 - t1)
-        per_row = max(b - a, 0.0) / n1
-        fixed = max(a - per_row * n1, 0.0)
-        step_s = fixed + per_row * cfg.video_tokens
-        sample = (f"fp32 oracle forward of the block on {n1} and {2 * n1} sampled query rows (keys/values of all "
-                  f"{cfg.seq_tokens} tokens), extrapolated affinely to {cfg.video_tokens} rows; measured "
-                  f"{a:.1f}s + {b:.1f}s")
+        # the whole block, every row: one forward of the workload's one sample is the whole step
+        # (about half a minute on 16 host threads; the update itself is negligible)
+        t0 = time.perf_counter()
+        dit.forward(cfg, W32, lat[0].astype(np.float32), cond[0].astype(np.float32), 500, dtype=None)
+        step_s = time.perf_counter() - t0
+        sample = (f"fp32 oracle forward of the whole block, all {cfg.video_tokens} rows, once ({step_s:.1f}s): "
+                  f"one step of the workload, nothing extrapolated")
     else:
         # one forward of one sample (through at most 28 blocks: about 10 s at the 1152-wide
         # shapes), scaled to depth and batch
@@ -96,6 +93,36 @@ def cpu_baseline(w, weights, lat, cond):
         pass
     return {"value": 1.0 / step_s, "unit": "steps/s", "cores": int(cores), "kind": "oracle", "sample": sample,
             "host_cpus": os.cpu_count() or 0, "cpu_model": cpu_model}
+
+
+def resume_cfg5a(k=10):
+    """One fc_denoise_resume call of the cfg5a workload (4 requests x guidance pair, 28 blocks of
+    the 1152-wide factorized model, 50-step schedule) from step k, wall clock."""
+    import torch
+    import paper_2501_04012_amd as fc
+    from paper_2501_04012_amd import synth
+    w = synth.WORKLOADS["cfg5a"]
+    cfg = w.model
+    weights = synth.make_weights(cfg, w.weight_seed)
+    lat, cond, null = synth.workload_inputs(w)
+    den = fc.Denoiser(cfg, weights, lat.shape[0], True)
+    del weights
+    d_cond, d_null = torch.from_numpy(cond).cuda(), torch.from_numpy(null).cuda()
+    d_lat0 = torch.from_numpy(lat).cuda()
+    d_lat = d_lat0.clone()
+    den.resume(d_lat, d_cond, d_null, w.schedule, w.schedule.num_steps - 2)       # warm-up: two steps
+    d_lat.copy_(d_lat0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    den.resume(d_lat, d_cond, d_null, w.schedule, k)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3
+    n = w.schedule.num_steps - k
+    forwards = lat.shape[0] * 2
+    tflops = synth.forward_flops(cfg)["total"] * forwards * n / (ms * 1e-3) / 1e12
+    den.close()
+    return {"k": k, "steps": n, "requests": int(lat.shape[0]), "ms": ms, "ms_per_step": ms / n, "tflops": tflops,
+            "pct_peak": 100.0 * tflops / PEAK_BF16_TFLOPS}
 
 
 def cache_restore_bench(args):
@@ -315,6 +342,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-resume", action="store_true",
+                    help="skip the whole cfg5a resume call that the default (cfg4) line also reports")
     ap.add_argument("--cache-restore", action="store_true",
                     help="time the cache-restore entry points instead of a denoising workload")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -468,8 +497,9 @@ def main():
             kernels[k]["gbps"] = nbytes / (kernels[k]["ms_per_step"] * 1e-3) / 1e9
     if dom in per_launch_flops:
         ach = per_launch_flops[dom] / (dom_launch_ms * 1e-3) / 1e12
+        traffic, traffic_source = measured_traffic(dom)
         roofline = {"kernel": dom, "bound": "mfma", "achieved": ach, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": ach / PEAK_BF16_TFLOPS, "traffic": measured_traffic(dom),
+                    "frac": ach / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_source": traffic_source,
                     "avg_launch_ms": dom_launch_ms, "launches": int(dom_cnt)}
     else:
         roofline = {"kernel": dom, "bound": "hbm", "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s",
@@ -494,6 +524,12 @@ def main():
     if resume:
         out["resume"] = resume
     den.close()
+    if args.workload == "cfg4" and not args.no_resume:
+        # the computation the cache resumes, beside the headline block: one whole
+        # fc_denoise_resume of the 28-block stack from k = 10 (4 requests x guidance pair)
+        del den, d_lat, d_lat0, d_cond
+        torch.cuda.empty_cache()
+        out["resume_cfg5a"] = resume_cfg5a()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, weights, lat, cond)
     print(json.dumps(out))

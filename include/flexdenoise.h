@@ -273,6 +273,17 @@ int fc_cache_select_key_frames(const float* sim, int32_t frames, float threshold
 int fc_op_linear(int32_t dtype, const void* A, const void* Wt, const float* bias, const float* gate,
                  void* out, int32_t M, int32_t N, int32_t K, int32_t epilogue, void* hip_stream);
 
+/* fc_op_linear with scratch memory lent by the caller (dev, 16-byte aligned, scratch_bytes;
+ * contents undefined afterwards), as the linear layers run inside a step: when the tiles of
+ * the product leave a last round that fills at most half the chip, that round's tiles are
+ * split along K, their fp32 partial tiles (at most 128 tiles x 2 ranges or 64 x 4, of 256 x 256
+ * floats: 64 MB) pass through the scratch and a second launch adds them in a
+ * fixed order and applies the epilogue.  Too little scratch: the product runs unsplit.
+ * Same result as fc_op_linear up to the order of the fp32 additions along K. */
+int fc_op_linear_scratch(int32_t dtype, const void* A, const void* Wt, const float* bias, const float* gate,
+                         void* out, int32_t M, int32_t N, int32_t K, int32_t epilogue, void* scratch,
+                         size_t scratch_bytes, void* hip_stream);
+
 /* Unmasked softmax(q k^T / sqrt(d)) v for G independent problems (one per
  * sequence and head).  q [G, nq, d], k [G, nk, d], v [G, nk, d], out [G, nq, d]
  * (all act).  impl 0: library's choice, 1: force the plain (non-MFMA) kernel.

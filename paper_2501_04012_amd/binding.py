@@ -70,6 +70,8 @@ EXPORTS = {
     "fc_profile_read": [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_int64)],
     "fc_op_linear": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                      C.c_int32, C.c_int32, C.c_void_p],
+    "fc_op_linear_scratch": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                             C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p],
     "fc_op_attention": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                         C.c_int32, C.c_int32, C.c_void_p],
     "fc_op_attention_bounded": [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
@@ -288,6 +290,12 @@ def fc_profile_read(model: int):
 def fc_op_linear(dtype, A, Wt, bias, gate, out, M, N, K, epilogue, stream=None) -> None:
     _check(_lib.fc_op_linear(dtype, _ptr(A), _ptr(Wt), _ptr(bias), _ptr(gate), _ptr(out), M, N, K, epilogue,
                              _stream(stream)), "fc_op_linear")
+
+
+def fc_op_linear_scratch(dtype, A, Wt, bias, gate, out, M, N, K, epilogue, scratch, stream=None) -> None:
+    nbytes = 0 if scratch is None else scratch.numel() * scratch.element_size()
+    _check(_lib.fc_op_linear_scratch(dtype, _ptr(A), _ptr(Wt), _ptr(bias), _ptr(gate), _ptr(out), M, N, K, epilogue,
+                                     _ptr(scratch), nbytes, _stream(stream)), "fc_op_linear_scratch")
 
 
 def fc_op_attention(dtype, q, k, v, out, G, nq, nk, d, impl=0, stream=None) -> None:

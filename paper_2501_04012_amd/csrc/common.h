@@ -263,8 +263,10 @@ hipError_t launch_cfg_ddim(float* x, const float* eps_c, const float* eps_u, flo
 hipError_t launch_cfg_ddim_noise(float* x, const float* eps_c, const float* eps_u, float* eps_out, size_t per_request,
                                  int requests, float gscale, float c0, float c1, float c2, float c3, float sigma,
                                  unsigned long long seed, int step, hipStream_t s);
+// scratch (optional, dev, 16-byte aligned): memory the product may use for split-K partial tiles
+// (fp32, at most 64 MB); without it every tile is computed whole
 hipError_t launch_gemm(int bf16, int mode, const void* A, const void* Wt, int M, int N, int K,
-                       const EpiParams& ep, hipStream_t s);
+                       const EpiParams& ep, hipStream_t s, void* scratch = nullptr, size_t scratch_bytes = 0);
 hipError_t launch_attention(int bf16, const AttnParams& p, int impl, hipStream_t s);
 // out [KB * heads * kKeyNormChunks] (f32): per (key batch, head) and chunk of the k_tokens rows of
 // k [KB, heads, k_tokens, hd] (bf16), the largest Euclidean row norm (0 for an empty chunk)

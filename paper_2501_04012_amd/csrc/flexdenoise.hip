@@ -292,6 +292,7 @@ struct Ctx {
   // Used when the text rows have their own modulation set: the gate then depends on the row.
   mutable const float* pending_gate = nullptr;
   int alt_rows() const { return m->cfg.text_adaln ? m->cfg.text_len : 0; }
+  size_t act_bytes() const { return (size_t)w.B * m->Ns * m->cfg.hidden * m->esz; }   // one of u, q, k, v
   int alt_off() const { return 6 * m->cfg.hidden; }
 };
 
@@ -314,10 +315,12 @@ struct ProfScope {        // records an event pair around the launches made in i
   }
 };
 
-int linear(const Ctx& c, int cat, int mode, const void* A, const Linear& L, int M, EpiParams ep) {
+// scratch: a workspace buffer that is dead while this product runs (split-K partial tiles)
+int linear(const Ctx& c, int cat, int mode, const void* A, const Linear& L, int M, EpiParams ep,
+           void* scratch = nullptr, size_t scratch_bytes = 0) {
   ep.bias = L.b;
   ProfScope ps(c, cat);
-  HIP_TRY(launch_gemm(c.m->bf16, mode, A, L.wt, M, L.out, L.in, ep, c.s));
+  HIP_TRY(launch_gemm(c.m->bf16, mode, A, L.wt, M, L.out, L.in, ep, c.s, scratch, scratch_bytes));
   return FC_OK;
 }
 
@@ -375,7 +378,8 @@ int branch_out(const Ctx& c, int cat, const void* A, const Linear& L, const floa
   EpiParams ep;
   const bool by_row = c.m->cfg.text_adaln != 0;      // the fold picks the row's gate instead
   ep.out = c.w.q; ep.ldo = c.m->cfg.hidden; ep.gate = by_row ? nullptr : gate;
-  int rc = linear(c, cat, EPI_GATE, A, L, c.w.B * c.m->Ns, ep);
+  // k is dead by now (attention is over; the MLP never used it) and is neither operand nor output here
+  int rc = linear(c, cat, EPI_GATE, A, L, c.w.B * c.m->Ns, ep, c.w.k, c.act_bytes());
   c.pending = rc == FC_OK;
   c.pending_gate = by_row ? gate : nullptr;
   return rc;
@@ -387,7 +391,9 @@ int self_attention_branch(const Ctx& c, const Linear& qkv, const Linear& proj, c
   const fc_model_config& cf = m->cfg;
   const Workspace& w = c.w;
   const int rows = w.B * m->Ns;
-  int rc = linear(c, PC_GEMM_QKV, EPI_HEADS, w.u, qkv, rows, heads_epi(c, w.q, w.k, w.v, 0, m->Ns));
+  // hid is dead between the MLP of the previous block and this block's MLP
+  int rc = linear(c, PC_GEMM_QKV, EPI_HEADS, w.u, qkv, rows, heads_epi(c, w.q, w.k, w.v, 0, m->Ns), w.hid,
+                  (size_t)rows * cf.mlp_dim * m->esz);
   if (rc != FC_OK) return rc;
   AttnParams ap{};
   ap.q = w.q; ap.k = w.k; ap.v = w.v; ap.out = w.u;
@@ -445,7 +451,7 @@ int mlp_branch(const Ctx& c, const Block& b, const float* mod) {
   if (rc != FC_OK) return rc;
   EpiParams e1;
   e1.out = c.w.hid; e1.ldo = m->cfg.mlp_dim;
-  rc = linear(c, PC_GEMM_FC1, EPI_GELU, c.w.u, b.fc1, rows, e1);
+  rc = linear(c, PC_GEMM_FC1, EPI_GELU, c.w.u, b.fc1, rows, e1, c.w.k, c.act_bytes());   // q, k, v are dead here
   if (rc != FC_OK) return rc;
   return branch_out(c, PC_GEMM_FC2, c.w.hid, b.fc2, mod + 2 * D);
 }
@@ -809,6 +815,19 @@ int fc_op_linear(int32_t dtype, const void* A, const void* Wt, const float* bias
   ep.bias = bias; ep.out = out; ep.ldo = N; ep.gate = gate;
   const int mode = epilogue == 0 ? EPI_STORE : epilogue == 1 ? EPI_GELU : EPI_GATE;
   HIP_TRY(launch_gemm(dtype == FC_BF16, mode, A, Wt, M, N, K, ep, (hipStream_t)stream));
+  return FC_OK;
+}
+
+int fc_op_linear_scratch(int32_t dtype, const void* A, const void* Wt, const float* bias, const float* gate, void* out,
+                         int32_t M, int32_t N, int32_t K, int32_t epilogue, void* scratch, size_t scratch_bytes,
+                         void* stream) {
+  if (!A || !Wt || !out) return fail(FC_ERR_NULL, "NULL argument");
+  if (M < 0 || N < 0 || K < 0 || epilogue < 0 || epilogue > 2) return fail(FC_ERR_RANGE, "bad size or epilogue");
+  if (scratch && ((uintptr_t)scratch & 15) != 0) return fail(FC_ERR_RANGE, "scratch must be 16-byte aligned");
+  EpiParams ep;
+  ep.bias = bias; ep.out = out; ep.ldo = N; ep.gate = gate;
+  const int mode = epilogue == 0 ? EPI_STORE : epilogue == 1 ? EPI_GELU : EPI_GATE;
+  HIP_TRY(launch_gemm(dtype == FC_BF16, mode, A, Wt, M, N, K, ep, (hipStream_t)stream, scratch, scratch_bytes));
   return FC_OK;
 }
 

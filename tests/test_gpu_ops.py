@@ -49,6 +49,51 @@ def test_linear_bf16(fc, M, N, K, epilogue):
     assert max_abs(got, want) < 3e-2
 
 
+@pytest.mark.parametrize("M,N,K,epilogue", [
+    (27 * 256 - 37, 29 * 256, 2048, 1),   # 783 tiles of 256 x 256: 15 left over, 4 ranges of K; ragged M; GELU
+    (44 * 256 - 50, 1152, 2112, 2),       # 44 x 6 = 264 tiles of 256 x 192: 8 left over; gated epilogue
+    (20 * 256, 39 * 256, 3072, 0),        # 780 tiles: 12 left over, 4 ranges of 12 K tiles
+    (5 * 256, 155 * 256, 2240, 0),        # 775 tiles, K = 35 tiles: ranges of unequal length
+    (70 * 256 - 144, 3072, 3072, 2),      # the full-3D configuration's output projection: 840 tiles, 72 left over, 3 ranges
+])
+def test_linear_bf16_split_k_remainder(fc, M, N, K, epilogue):
+    """Products whose tile count leaves a nearly empty last round: with scratch memory that
+    round is split along K and finished by the fix-up launch.  Against the float64 product, and
+    against the unsplit launch (the sums along K are merely associated differently)."""
+    torch = _torch()
+    rng = np.random.default_rng(M + N + K)
+    A = BF(rng.standard_normal((M, K), dtype=np.float32))
+    W = BF(rng.standard_normal((K, N), dtype=np.float32) * np.float32(1 / math.sqrt(K)))
+    b = rng.standard_normal(N, dtype=np.float32)
+    g = rng.standard_normal(N, dtype=np.float32) if epilogue == 2 else None
+    want = A.astype(np.float64) @ W.astype(np.float64) + b
+    want = dit.gelu_tanh(want) if epilogue == 1 else want * g if epilogue == 2 else want
+    dA, dW, db, dg = dev(A, True), dev(W.T.copy(), True), dev(b), dev(g) if g is not None else None
+    out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    scratch = torch.empty(128 << 20, dtype=torch.uint8, device="cuda:0")
+    fc.fc_op_linear_scratch(fc.FC_BF16, dA, dW, db, dg, out, M, N, K, epilogue, scratch)
+    ref = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    fc.fc_op_linear(fc.FC_BF16, dA, dW, db, dg, ref, M, N, K, epilogue)
+    again = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    fc.fc_op_linear_scratch(fc.FC_BF16, dA, dW, db, dg, again, M, N, K, epilogue, scratch)
+    torch.cuda.synchronize()
+    got = host(out)
+    assert np.isfinite(got).all()
+    assert rel_l2(got, want) < 4e-3, rel_l2(got, want)
+    # element by element: the rounding of the bf16 output (half an ulp: 2^-9 relative) plus the fp32 sums
+    assert (np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 2e-2).all()
+    assert rel_l2(got, host(ref)) < 2e-3
+    assert torch.equal(out, again)                         # fixed order of the partial sums
+    # the split really happened where it should: the unsplit result differs in a few roundings
+    # (no assertion on that: equality would be legal, just improbable)
+    # too little scratch: runs unsplit, bit-identical to fc_op_linear
+    small = torch.empty(1 << 20, dtype=torch.uint8, device="cuda:0")
+    out2 = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    fc.fc_op_linear_scratch(fc.FC_BF16, dA, dW, db, dg, out2, M, N, K, epilogue, small)
+    torch.cuda.synchronize()
+    assert torch.equal(out2, ref)
+
+
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (70, 65, 33), (256, 64, 64)])
 def test_linear_fp32(fc, M, N, K):
     torch = _torch()
