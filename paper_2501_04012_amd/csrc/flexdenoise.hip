@@ -349,7 +349,9 @@ int prepare(const Ctx& c, const float* cond, const float* null_cond) {
   }
   EpiParams ep;
   ep.out = w.y; ep.ldo = cf.hidden;
-  int rc = linear(c, PC_GEMM_OTHER, EPI_STORE, w.txt, m->y, w.NT * cf.text_len, ep);
+  // few rows, long K: split along K through hid, which nothing uses before the first block's MLP
+  int rc = linear(c, PC_GEMM_OTHER, EPI_STORE, w.txt, m->y, w.NT * cf.text_len, ep, w.hid,
+                  (size_t)w.B * m->Ns * cf.mlp_dim * m->esz);
   if (rc != FC_OK) return rc;
   if (cf.attn_mode == FC_ATTN_FACTORIZED_CROSS) {
     for (int l = 0; l < cf.depth; ++l) {

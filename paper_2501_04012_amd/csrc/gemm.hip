@@ -517,8 +517,8 @@ static hipError_t run_dlds(const void* A, const void* Wt, int M, int N, int K, c
   // the fix-up launch, and a caller that lends scratch memory for the partial tiles.
   int splits = 1;
   const long long rem = total % 256;
-  if (slots == 256 && total > 256 && total / 256 <= 8 && rem > 0 && rem <= 128 && scratch &&
-      ((uintptr_t)scratch & 15) == 0) {
+  // (A product of fewer than 128 tiles is all remainder: its tiles are split the same way.)
+  if (grid == 256 && total / 256 <= 8 && rem > 0 && rem <= 128 && scratch && ((uintptr_t)scratch & 15) == 0) {
     long long sp = 256 / rem;
     sp = sp > 4 ? 4 : sp;
     sp = sp > K / BK ? K / BK : sp;
@@ -584,7 +584,7 @@ static hipError_t dispatch_mode(int bf16, const void* A, const void* Wt, int M, 
   if (N % 192 == 0 && waste > 0.05 && (long long)ceil_div(M, 256) * (N / 192) >= 192)
     return run_dlds<256, 192, 64, 4, 2, 2, MODE>(A, Wt, M, N, K, ep, scratch, scratch_bytes, s);
   if (tiles256 >= 600 && (waste <= 0.05 || K >= 2048)) return run_dlds<256, 256, 64, 4, 2, 2, MODE>(A, Wt, M, N, K, ep, scratch, scratch_bytes, s);
-  return run_dlds<128, 128, 64, 2, 2, 2, MODE>(A, Wt, M, N, K, ep, nullptr, 0, s);
+  return run_dlds<128, 128, 64, 2, 2, 2, MODE>(A, Wt, M, N, K, ep, scratch, scratch_bytes, s);
 }
 
 hipError_t launch_gemm(int bf16, int mode, const void* A, const void* Wt, int M, int N, int K, const EpiParams& ep,

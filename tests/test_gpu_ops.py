@@ -55,6 +55,8 @@ def test_linear_bf16(fc, M, N, K, epilogue):
     (20 * 256, 39 * 256, 3072, 0),        # 780 tiles: 12 left over, 4 ranges of 12 K tiles
     (5 * 256, 155 * 256, 2240, 0),        # 775 tiles, K = 35 tiles: ranges of unequal length
     (70 * 256 - 144, 3072, 3072, 2),      # the full-3D configuration's output projection: 840 tiles, 72 left over, 3 ranges
+    (226, 3072, 4096, 0),                 # its text projection: 48 tiles of 128 x 128, all of them split in 4
+    (1000, 1152, 3072, 1),                # 72 tiles of 128 x 128, ragged M, 3 ranges
 ])
 def test_linear_bf16_split_k_remainder(fc, M, N, K, epilogue):
     """Products whose tile count leaves a nearly empty last round: with scratch memory that
