@@ -5,11 +5,15 @@
 //         launch-bound; it exists for the 1e-4 parity bar, not for speed).
 // Both operands are contiguous along K ("TN" form): activations are [tokens, K]
 // and weights are stored [out, in].
+#include <type_traits>
 #include "common.h"
 
 namespace fc {
 
 // ---------------------------------------------------------------- bf16 MFMA kernel, direct-to-LDS
+// (k_gemm_dlds_any: the general form, any K that is a multiple of 64 and operands of any size.
+// k_gemm_dlds further down is the one the workloads run; what is said here about tiles, layout,
+// tile order and units of work holds for both.)
 // Block tile BM x BN x BK, NW = WR x WC waves, each wave owns a (BM/WR) x (BN/WC) tile built
 // from 32x32 MFMA accumulators.  MFMA operand layout (32x32x16, wave64), lane = i + 32*h:
 //   A: row i of the 32-row tile, k = 8h .. 8h+7        (8 bf16 = one 16-byte LDS read)
@@ -145,7 +149,7 @@ __device__ __forceinline__ void gemm_tile_epilogue(const f32x16 (&acc)[BM / WR /
 }
 
 template <int BM, int BN, int BK, int WR, int WC, int S, typename Epi>
-__global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __restrict__ A,
+__global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds_any(const bf16_t* __restrict__ A,
                                                             const bf16_t* __restrict__ Wt, int M, int N, int K,
                                                             int tiles_m, int tiles_n, Epi epi, int splits,
                                                             float* __restrict__ partial) {
@@ -358,6 +362,275 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
   }
 }
 
+// ---------------------------------------------------------------- the product kernel
+// Same tiles, LDS layout, tile order and epilogue as k_gemm_dlds_any above (which stays for the
+// shapes this one does not take), with two changes to the K loop.
+//
+// Addresses are buffer offsets.  A lane's byte offset inside a 256-row operand panel is the
+// same for every tile and every K tile: the tile enters through the base of a buffer resource
+// rebuilt per tile in scalar registers, the K tile through the scalar offset of the load.  The
+// per-lane pointer arrays of k_gemm_dlds_any (32 registers, recomputed per tile, advanced per
+// K tile with 64-bit vector adds) are gone, and so are the clamps at the ragged edges: rows
+// past the end of an operand are out of the resource's range and load as zero.
+//
+// The barrier that publishes K tile g + 1 sits before the MFMAs of g's last k-slice, whose
+// fragments are in registers by then.  After it a wave requests K tile g + 2 into the stage it
+// has just stopped reading, reads the first fragments of g + 1, and only then multiplies g's
+// last slice: neither the requests nor the LDS latency of the first fragments find the matrix
+// pipe empty, and a DMA still has a whole K tile of matrix work to land.
+//
+// Measured against k_gemm_dlds_any in one process, bit-identical results: 5-11 % faster on the
+// products of the two large configurations (K = 1152 .. 3072), 5 % at K = 12288, level at
+// 256x192 with K = 4608, 5-10 % on the 128x128 products of a single block.
+//
+// Needs an even number of K tiles (the stage of a K tile is a compile-time constant: units
+// start at stage 0) and operands below 4 GB (32-bit buffer ranges).
+// s_waitcnt vmcnt(N) lgkmcnt(0)
+template <int N> __device__ __forceinline__ void wait_vm_lgkm0() {
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4));
+}
+template <int BM, int BN, int BK, int WR, int WC, typename Epi>
+__global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __restrict__ A, const bf16_t* __restrict__ Wt,
+                                                           int M, int N, int K, int tiles_m, int tiles_n, Epi epi,
+                                                           int splits, float* __restrict__ partial) {
+#if defined(__HIP_DEVICE_COMPILE__)   // buffer resources are a device-side type: the host pass sees an empty body
+  constexpr int NW = WR * WC;
+  constexpr int WTM = BM / WR, WTN = BN / WC;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  static_assert(BK == 64, "128-byte rows");
+  constexpr int CPR = BK / 8, RPL = 16 / CPR, RW = 4 * RPL;
+  constexpr int LA = BM / RW / NW, LB = BN / RW / NW;      // wave-loads per wave and K tile: rows of A, rows of Wt
+  static_assert(BM % (RW * NW) == 0 && BN % (RW * NW) == 0, "loads must divide among waves");
+  static_assert(LB <= LA, "B shares A's lane offsets");
+  static_assert((NW * 4) % CPR == 0 && (BM / RW * 4) % CPR == 0, "the swizzle must not depend on the load index");
+  constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
+  constexpr int B_REGION = BM * BK * 2;
+  constexpr int KS = BK / 16;
+
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  float* const sbias = (float*)(smem + 2 * STAGE_BYTES);
+  float* const sgate = sbias + 256;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave / WC, wc = wave % WC;
+  const int li = lane & 31, lh = lane >> 5;
+
+  // ---- units of work (as in k_gemm_dlds_any; split ranges start at even K tiles)
+  const int total = tiles_m * tiles_n;
+  const int padded = (total + 255) / 256 * 256;
+  const int nkt = K / BK;
+  const int full = total / 256 * 256, rem = total - full;
+  auto tile_of = [&](int vb, int& bm0, int& bn0, int& kt0, int& kt1, int& slot) {
+    const int xcd = vb & 7, local = vb >> 3;
+    int t = ((local >> 5) * 8 + xcd) * 32 + (local & 31);
+    kt0 = 0; kt1 = nkt; slot = -1;
+    if (splits >= 2 && vb >= full) {
+      const int w = vb - full;
+      if (w >= rem * splits) return false;
+      const int r = w / rem;
+      t = full + w % rem;
+      kt0 = (r * nkt / splits) & ~1; kt1 = r + 1 == splits ? nkt : ((r + 1) * nkt / splits) & ~1;   // even: see the K loop
+      slot = (w % rem) * splits + r;
+    }
+    if (t >= total) return false;
+    constexpr int GM = 8;
+    const int per_group = GM * tiles_n;
+    const int group = t / per_group;
+    const int first_m = group * GM;
+    const int gsz = min(tiles_m - first_m, GM);
+    bm0 = (first_m + (t % per_group) % gsz) * BM;
+    bn0 = ((t % per_group) / gsz) * BN;
+    return true;
+  };
+  auto next_tile = [&](int& vb, int& bm0, int& bn0, int& kt0, int& kt1, int& slot) {
+    for (vb += gridDim.x; vb < padded; vb += gridDim.x)
+      if (tile_of(vb, bm0, bn0, kt0, kt1, slot)) return true;
+    return false;
+  };
+
+  // ---- this lane's byte offsets inside an operand panel, one per wave-load (the swizzled
+  // 16-byte chunk of row (wave + NW j) RW + ... that lands in its LDS slot)
+  unsigned voff[LA];
+  {
+    const int line_in = lane >> 4, sl = lane & 15;
+    const int row0 = wave * RW + line_in * RPL + sl / CPR;
+    const int kc = (sl % CPR) ^ ((wave * 4 + line_in) % CPR);
+#pragma unroll
+    for (int j = 0; j < LA; ++j) voff[j] = (unsigned)(row0 + NW * RW * j) * (unsigned)K * 2u + (unsigned)kc * 16u;
+  }
+  struct Panels { __amdgpu_buffer_rsrc_t a, b; int kbase; };
+  auto panels = [&](int bm0, int bn0, int kt_first) {
+    Panels p;
+    p.a = __builtin_amdgcn_make_buffer_rsrc((void*)(A + (size_t)bm0 * K), 0, (int)((unsigned)(M - bm0) * (unsigned)K * 2u), 0x00020000);
+    p.b = __builtin_amdgcn_make_buffer_rsrc((void*)(Wt + (size_t)bn0 * K), 0, (int)((unsigned)(N - bn0) * (unsigned)K * 2u), 0x00020000);
+    p.kbase = kt_first * BK * 2;
+    return p;
+  };
+  auto dma_a = [&](const Panels& p, int kt, int stage) {
+#pragma unroll
+    for (int j = 0; j < LA; ++j)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(p.a, (lds_void*)(smem + stage * STAGE_BYTES + (wave + NW * j) * 1024), 16, (int)voff[j],
+                                               p.kbase + kt * (BK * 2), 0, 0);
+  };
+  auto dma_b = [&](const Panels& p, int kt, int stage) {
+#pragma unroll
+    for (int j = 0; j < LB; ++j)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(p.b, (lds_void*)(smem + stage * STAGE_BYTES + B_REGION + (wave + NW * j) * 1024), 16,
+                                               (int)voff[j], p.kbase + kt * (BK * 2), 0, 0);
+  };
+  auto issue_vectors = [&](int bn0) {
+    if constexpr (Epi::kRowRuns) {
+      int n = bn0 + lane * 4;
+      n = n < N ? n : 0;                           // columns past N are never stored
+      if (wave == 0 && epi.P.bias)
+        __builtin_amdgcn_global_load_lds((gbl_void*)(epi.P.bias + n), (lds_void*)sbias, 16, 0, 0);
+      if (Epi::kHasGate && wave == 1 && epi.P.gate)
+        __builtin_amdgcn_global_load_lds((gbl_void*)(epi.P.gate + n), (lds_void*)sgate, 16, 0, 0);
+    }
+  };
+
+  // ---- fragment read offsets (bytes within a stage)
+  const int ra = wr * WTM + li, rb = BM + wc * WTN + li;
+  const int a_row = (ra / RPL) * 256 + (ra % RPL) * CPR * 16, a_x = (ra / RPL) % CPR;
+  const int b_row = (rb / RPL) * 256 + (rb % RPL) * CPR * 16, b_x = (rb / RPL) % CPR;
+  constexpr int TILE_STRIDE = (32 / RPL) * 256;   // 32 rows further down
+
+  int vb = (int)blockIdx.x - (int)gridDim.x, bm0 = 0, bn0 = 0, kt0 = 0, kt1 = 0, slot = -1;
+  if (!next_tile(vb, bm0, bn0, kt0, kt1, slot)) return;
+  Panels cur = panels(bm0, bn0, kt0);
+  int nk = kt1 - kt0;                              // K tiles of the current unit, at least 2
+
+  // K tiles are numbered g = 0, 1, ... across this workgroup's units; K tile g is multiplied
+  // out of stage g & 1.
+  dma_a(cur, 0, 0);
+  dma_b(cur, 0, 0);
+  wait_vm<0>();
+  __builtin_amdgcn_s_barrier();
+  int g = 0;
+
+  constexpr int kDsRead = 0x100, kMfma = 0x008, kVmem = 0x010;
+  for (;;) {
+    int nvb = vb, nbm0 = 0, nbn0 = 0, nkt0 = 0, nkt1 = 0, nslot = -1;
+    const bool has_next = next_tile(nvb, nbm0, nbn0, nkt0, nkt1, nslot);
+    Panels nxt = cur;
+    if (has_next) nxt = panels(nbm0, nbn0, nkt0);
+    issue_vectors(bn0);                            // awaited and published with the unit's first K tile
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    bf16x8 fa[2][TM], fb[2][TN];
+    auto load = [&](int stage, int ks, bf16x8 (&xa)[TM], bf16x8 (&xb)[TN]) {
+      const unsigned char* st = smem + stage * STAGE_BYTES;
+      const unsigned char* pa = st + a_row + (((2 * ks + lh) ^ a_x) << 4);
+      const unsigned char* pb = st + b_row + (((2 * ks + lh) ^ b_x) << 4);
+#pragma unroll
+      for (int i = 0; i < TM; ++i) xa[i] = *(const bf16x8*)(pa + i * TILE_STRIDE);
+#pragma unroll
+      for (int j = 0; j < TN; ++j) xb[j] = *(const bf16x8*)(pb + j * TILE_STRIDE);
+    };
+    auto multiply = [&](int set) {
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          // row-run epilogues want a lane to hold consecutive n: D rows come from the A
+          // operand, so the weight fragment goes there (the operand layouts are alike)
+          acc[i][j] = Epi::kRowRuns ? __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[set][j], fa[set][i], acc[i][j], 0, 0, 0)
+                                    : __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[set][i], fb[set][j], acc[i][j], 0, 0, 0);
+    };
+    // requests K tile ka of this unit into `stage`, continuing into the next unit past the end;
+    // past the last K tile of the last unit K tile 0 of the current panels is requested again
+    // (in range, never read) rather than branching around the loads
+    auto request = [&](int ka, int stage) {
+      const bool ina = ka < nk;
+      const Panels& pa = ina ? cur : nxt;
+      const int k = ina ? ka : (has_next ? ka - nk : 0);
+      dma_a(pa, k, stage);
+      dma_b(pa, k, stage);
+    };
+
+    // One K tile.  PAR = g & 1 selects the stage at compile time: every unit has an even number
+    // of K tiles (the dispatcher sends other K to k_gemm_dlds_any), so a unit always starts at
+    // PAR 0.  FIRST: the unit's first K tile (its successor not requested yet, no fragments in
+    // registers: the only reads of a unit with no matrix work in front of them); LAST: its last
+    // one (no requests: the stage it frees is where the epilogue stages its output rows).
+    auto kstep = [&](auto par, auto first, auto last, int kt) {
+      constexpr int PAR = decltype(par)::value;
+      constexpr bool FIRST = decltype(first)::value, LAST = decltype(last)::value;
+      if constexpr (FIRST) {
+        request(kt + 1, PAR ^ 1);
+        load(PAR, 0, fa[0], fb[0]);
+        __builtin_amdgcn_sched_group_barrier(kVmem, LA + LB, 0);
+        __builtin_amdgcn_sched_group_barrier(kDsRead, TM + TN, 0);
+      }
+      // k-slices 0 .. KS-2; the fragments of slice ks + 1 are read under the MFMAs of slice ks,
+      // the order pinned (left alone the compiler emits read-all / wait / multiply per slice)
+#pragma unroll
+      for (int ks = 0; ks + 1 < KS; ++ks) {
+        load(PAR, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+        multiply(ks & 1);
+      }
+#pragma unroll
+      for (int ks = 0; ks + 1 < KS; ++ks) {
+#pragma unroll
+        for (int r = 0; r < TM + TN; ++r) {
+          __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+          __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);
+        }
+        if (TM * TN > TM + TN) __builtin_amdgcn_sched_group_barrier(kMfma, TM * TN - (TM + TN), 0);
+      }
+      wait_vm_lgkm0<0>();                          // K tile g + 1 has landed; this wave is done reading g
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (!LAST) {
+        request(kt + 2, PAR);
+        load(PAR ^ 1, 0, fa[0], fb[0]);
+      }
+      multiply((KS - 1) & 1);
+      if constexpr (!LAST) {
+        constexpr int PER = (LA + LB + TM * TN - 1) / (TM * TN);
+#pragma unroll
+        for (int r = 0; r < TM * TN; ++r) {
+          __builtin_amdgcn_sched_group_barrier(kMfma, 1, 0);
+          if (r < TM + TN) __builtin_amdgcn_sched_group_barrier(kDsRead, 1, 0);
+          if (r * PER < LA + LB) __builtin_amdgcn_sched_group_barrier(kVmem, PER, 0);
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+
+    using P0 = std::integral_constant<int, 0>; using P1 = std::integral_constant<int, 1>;
+    using Yes = std::true_type; using No = std::false_type;
+    kstep(P0{}, Yes{}, No{}, 0);
+    for (int kt = 1; kt + 1 < nk; kt += 2) {
+      kstep(P1{}, No{}, No{}, kt);
+      kstep(P0{}, No{}, No{}, kt + 1);
+    }
+    kstep(P1{}, No{}, Yes{}, nk - 1);
+    g += nk;
+
+    // every wave is done reading the stage just multiplied ((g - 1) & 1): the epilogue stages
+    // its output rows there; the next unit's first K tile is complete in the other stage
+    if (slot < 0) {
+      gemm_tile_epilogue<BM, BN, BK, WR, WC>(acc, smem + ((g - 1) & 1) * STAGE_BYTES, sbias, sgate, epi, bm0, bn0, M, N);
+    } else {
+      store_partial<TM, TN>(acc, partial + (size_t)slot * (BM * BN));
+    }
+    if (!has_next) break;
+    // the staging slices are read out: the next unit's second K tile may overwrite that stage
+    __builtin_amdgcn_s_barrier();
+    vb = nvb; bm0 = nbm0; bn0 = nbn0; nk = nkt1 - nkt0; slot = nslot;
+    cur = nxt;
+  }
+#endif
+}
+
 // ---------------------------------------------------------------- split-K fix-up
 // One workgroup per tile of the split round: adds the tile's `splits` partial accumulators in
 // range order (bitwise repeatable) and runs the product kernel's epilogue on the sum.
@@ -497,10 +770,15 @@ static hipError_t run_dlds(const void* A, const void* Wt, int M, int N, int K, c
   using Epi = Epilogue<bf16_t, MODE>;
   Epi epi = Epi::make(ep, M, N);
   constexpr size_t smem = (size_t)S * (BM + BN) * BK * sizeof(bf16_t) + 2048;   // + bias and gate of a tile
-  auto kern = k_gemm_dlds<BM, BN, BK, WR, WC, S, Epi>;
+  // k_gemm_dlds needs an even number of K tiles and addresses its operands as 32-bit buffer
+  // ranges; anything else goes to k_gemm_dlds_any
+  const bool even = K % (2 * BK) == 0 && (unsigned long long)M * K * 2 < (1ull << 32) && (unsigned long long)N * K * 2 < (1ull << 32);
+  auto kern = k_gemm_dlds<BM, BN, BK, WR, WC, Epi>;
+  auto kern_any = k_gemm_dlds_any<BM, BN, BK, WR, WC, S, Epi>;
   static bool attr_set = false;
   if (!attr_set) {
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+    if (e == hipSuccess) e = hipFuncSetAttribute((const void*)kern_any, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attr_set = true;
   }
@@ -526,8 +804,11 @@ static hipError_t run_dlds(const void* A, const void* Wt, int M, int N, int K, c
         (size_t)(rem * sp) * BM * BN * sizeof(float) <= scratch_bytes)
       splits = (int)sp;
   }
-  kern<<<grid, WR * WC * 64, smem, s>>>((const bf16_t*)A, (const bf16_t*)Wt, M, N, K, tiles_m, tiles_n, epi, splits,
-                                        (float*)scratch);
+  if (even)
+    kern<<<grid, WR * WC * 64, smem, s>>>((const bf16_t*)A, (const bf16_t*)Wt, M, N, K, tiles_m, tiles_n, epi, splits, (float*)scratch);
+  else
+    kern_any<<<grid, WR * WC * 64, smem, s>>>((const bf16_t*)A, (const bf16_t*)Wt, M, N, K, tiles_m, tiles_n, epi, splits,
+                                              (float*)scratch);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || splits < 2) return e;
   auto fix = k_gemm_fixup<BM, BN, BK, WR, WC, Epi>;

@@ -26,6 +26,9 @@ LIN_SHAPES = [
     (2500, 48, 192),         # narrow N, many rows (the output head's shape class), ragged both ways
     (8209, 2048, 128),       # enough tiles for the 256x256 configuration, ragged M
     (8200, 1152, 128),       # N a multiple of 192 that 256 would pad: the 256x192 configuration, ragged M
+    (8209, 2048, 192),       # an odd number of K tiles: the general form of the tile kernel, 256x256
+    (8200, 1152, 320),       # the same, 256x192
+    (8209, 2304, 384),       # six K tiles, 256x256, ragged M
     (250, 160, 72),          # K not a multiple of 64: plain kernel
 ]
 
