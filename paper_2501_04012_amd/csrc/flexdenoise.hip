@@ -519,7 +519,7 @@ int run_step(const Ctx& c, float* latent, const fc_schedule* sched, int step, fl
   }
   EpiParams ep;
   ep.eps = w.eps; ep.T = cf.frames; ep.H = cf.height; ep.W = cf.width; ep.C = cf.channels; ep.p = cf.patch;
-  if ((rc = linear(c, PC_GEMM_OTHER, EPI_UNPATCH, w.u, m->fout, w.B * m->N, ep)) != FC_OK) return rc;
+  if ((rc = linear(c, PC_GEMM_OTHER, EPI_UNPATCH, w.u, m->fout, w.B * m->N, ep, w.k, c.act_bytes())) != FC_OK) return rc;   // q, k, v are dead here
 
   const size_t n = (size_t)c.R * cf.frames * cf.height * cf.width * cf.channels;
   ProfScope ps(c, PC_CFG_DDIM);

@@ -189,9 +189,10 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds_any(const bf16_t* __
   // fixed order and finishes the tile.  A round that leaves most of the chip idle for the
   // time of a whole tile thus costs 1 / splits of it.
   const int total = tiles_m * tiles_n;
-  const int padded = (total + 255) / 256 * 256;
   const int nkt = K / BK;
   const int full = total / 256 * 256, rem = total - full;
+  // virtual ids run over the whole rounds and, behind them, the units of the last one
+  const int padded = splits >= 2 ? ((full + rem * splits + 7) & ~7) : (total + 255) / 256 * 256;
   auto tile_of = [&](int vb, int& bm0, int& bn0, int& kt0, int& kt1, int& slot) {
     const int xcd = vb & 7, local = vb >> 3;
     int t = ((local >> 5) * 8 + xcd) * 32 + (local & 31);
@@ -417,9 +418,10 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
 
   // ---- units of work (as in k_gemm_dlds_any; split ranges start at even K tiles)
   const int total = tiles_m * tiles_n;
-  const int padded = (total + 255) / 256 * 256;
   const int nkt = K / BK;
   const int full = total / 256 * 256, rem = total - full;
+  // virtual ids run over the whole rounds and, behind them, the units of the last one
+  const int padded = splits >= 2 ? ((full + rem * splits + 7) & ~7) : (total + 255) / 256 * 256;
   auto tile_of = [&](int vb, int& bm0, int& bn0, int& kt0, int& kt1, int& slot) {
     const int xcd = vb & 7, local = vb >> 3;
     int t = ((local >> 5) * 8 + xcd) * 32 + (local & 31);
@@ -794,20 +796,29 @@ static hipError_t run_dlds(const void* A, const void* Wt, int M, int N, int K, c
   // faster, 13.1 rounds not at all), a K long enough that the saved part of a tile outweighs
   // the fix-up launch, and a caller that lends scratch memory for the partial tiles.
   int splits = 1;
-  const long long rem = total % 256;
-  // (A product of fewer than 128 tiles is all remainder: its tiles are split the same way.)
-  if (grid == 256 && total / 256 <= 8 && rem > 0 && rem <= 128 && scratch && ((uintptr_t)scratch & 15) == 0) {
-    long long sp = 256 / rem;
+  unsigned launch = grid;
+  const long long rem = total % 256, full = total - rem;
+  // (A product of fewer tiles than half the slots is all remainder: its tiles are split the
+  // same way; with two workgroups per CU there are 512 slots for the units.)
+  // (With two workgroups per CU every product of up to 512 tiles runs in one round anyway: only
+  // the all-remainder case is split there.)
+  if (total / 256 <= 8 && rem > 0 && rem <= slots / 2 && (slots == 256 || full == 0) && scratch &&
+      ((uintptr_t)scratch & 15) == 0) {
+    long long sp = slots / rem;
     sp = sp > 4 ? 4 : sp;
-    sp = sp > K / BK ? K / BK : sp;
+    sp = sp > K / BK / 2 ? K / BK / 2 : sp;
     if (sp >= 2 && (long long)K * (sp - 1) / sp >= 1536 &&
-        (size_t)(rem * sp) * BM * BN * sizeof(float) <= scratch_bytes)
+        (size_t)(rem * sp) * BM * BN * sizeof(float) <= scratch_bytes) {
       splits = (int)sp;
+      const long long units = (full + rem * sp + 7) / 8 * 8;
+      launch = (unsigned)(units < slots ? units : slots);
+      if (launch < grid) launch = grid;
+    }
   }
   if (even)
-    kern<<<grid, WR * WC * 64, smem, s>>>((const bf16_t*)A, (const bf16_t*)Wt, M, N, K, tiles_m, tiles_n, epi, splits, (float*)scratch);
+    kern<<<launch, WR * WC * 64, smem, s>>>((const bf16_t*)A, (const bf16_t*)Wt, M, N, K, tiles_m, tiles_n, epi, splits, (float*)scratch);
   else
-    kern_any<<<grid, WR * WC * 64, smem, s>>>((const bf16_t*)A, (const bf16_t*)Wt, M, N, K, tiles_m, tiles_n, epi, splits,
+    kern_any<<<launch, WR * WC * 64, smem, s>>>((const bf16_t*)A, (const bf16_t*)Wt, M, N, K, tiles_m, tiles_n, epi, splits,
                                               (float*)scratch);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || splits < 2) return e;

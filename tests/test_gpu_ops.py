@@ -60,6 +60,8 @@ def test_linear_bf16(fc, M, N, K, epilogue):
     (70 * 256 - 144, 3072, 3072, 2),      # the full-3D configuration's output projection: 840 tiles, 72 left over, 3 ranges
     (226, 3072, 4096, 0),                 # its text projection: 48 tiles of 128 x 128, all of them split in 4
     (1000, 1152, 3072, 1),                # 72 tiles of 128 x 128, ragged M, 3 ranges
+    (17550, 64, 3072, 0),                 # the full-3D configuration's output head: 138 tiles of 128 x 128 (half of N empty), 3 ranges
+    (150 * 128 - 7, 128, 2048, 1),        # 150 tiles of 128 x 128: 3 ranges, 450 units on 512 slots
 ])
 def test_linear_bf16_split_k_remainder(fc, M, N, K, epilogue):
     """Products whose tile count leaves a nearly empty last round: with scratch memory that
