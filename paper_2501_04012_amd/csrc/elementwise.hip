@@ -330,18 +330,25 @@ __global__ __launch_bounds__(256) void k_patch_embed_mfma(const float* __restric
         acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_lo, w_hi[j][st], acc[j], 0, 0, 0);
       }
     }
+    // stores: a wave-uniform row pointer plus one per-lane offset (scalar address arithmetic), and
+    // no per-store predicate except in the one ragged tile of a frame
+    const unsigned lane_off = (unsigned)(4 * lh) * (unsigned)D + (unsigned)li;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
-      const int col = col0 + 32 * j + li;
-      const float pt = pos_t[(size_t)t * D + col];
-      float* xc = x + ((size_t)b * rows_per_b + row_off + (size_t)t * S) * D + col;
+      const float pt = pos_t[(size_t)t * D + col0 + 32 * j + li];
+      float* xu = x + ((size_t)b * rows_per_b + row_off + (size_t)t * S + s0) * D + col0 + 32 * j;
+      if (s0 + 32 <= S) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g)
+        for (int g = 0; g < 4; ++g)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int tok = s0 + 8 * g + 4 * lh + e;
-          if (tok < S) xc[(size_t)tok * D] = acc[j][4 * g + e] + pt;
-        }
+          for (int e = 0; e < 4; ++e) xu[(size_t)(8 * g + e) * D + lane_off] = acc[j][4 * g + e] + pt;
+      } else {
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (s0 + 8 * g + 4 * lh + e < S) xu[(size_t)(8 * g + e) * D + lane_off] = acc[j][4 * g + e] + pt;
+      }
     }
   }
 }
