@@ -100,6 +100,7 @@ struct Epilogue {
   FastDiv unp_S, unp_gw;       // EPI_UNPATCH
   FastDiv col_D, col_hd;       // EPI_HEADS, row-run form
   static constexpr bool kRowRuns = MODE != EPI_UNPATCH;
+  static constexpr bool kLinearOut = MODE == EPI_STORE || MODE == EPI_GELU || MODE == EPI_GATE;   // out[m * ldo + n]
   static constexpr bool kHasGate = MODE == EPI_GATE;
 
   // host side: fills the divisors the mode needs
@@ -156,8 +157,10 @@ struct Epilogue {
   // v: accumulators of columns n0..n0+3 (n0 % 4 == 0) of one row -> final values.
   // lbias / lgate: LDS copies of bias[n0..] and gate[n0..] (the tile's slices; garbage-free
   // for columns past Nvalid, which are never stored).
+  // (a kernel without a bias or a gate keeps zeros or ones in the LDS copies: no branch here,
+  // so that the reads of a whole pass can be issued together)
   __device__ __forceinline__ void apply4(int n0, float (&v)[4], const float* lbias, const float* lgate) const {
-    if (P.bias) {
+    {
       const f32x4 b = *(const f32x4*)lbias;
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] += b[e];
@@ -166,7 +169,7 @@ struct Epilogue {
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] = gelu_tanh_f(v[e]);
     } else if constexpr (MODE == EPI_GATE) {
-      if (P.gate) {
+      {
         const f32x4 g = *(const f32x4*)lgate;
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] *= g[e];
@@ -177,6 +180,8 @@ struct Epilogue {
       for (int e = 0; e < 4; ++e) v[e] *= sc;
     }
   }
+  // Row-major outputs: address of (m, n) for wave-uniform m and n
+  __device__ __forceinline__ T* row_ptr(int m, int n) const { return (T*)P.out + (size_t)m * P.ldo + n; }
   // Address of outputs (m, n0 .. n0+7), n0 % 8 == 0: one 16-byte run in every row-run mode.
   __device__ __forceinline__ T* run8(int m, int n0) const {
     if constexpr (MODE == EPI_HEADS) {

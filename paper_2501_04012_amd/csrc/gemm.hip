@@ -90,7 +90,13 @@ __device__ __forceinline__ void gemm_tile_epilogue(const f32x16 (&acc)[BM / WR /
   constexpr int WTM = BM / WR, WTN = BN / WC;
   constexpr int TM = WTM / 32, TN = WTN / 32;
   constexpr int STAGE_BYTES = (BM + BN) * BK * 2;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // The lane and wave numbers pass through an empty asm: everything derived from them here (LDS
+  // staging offsets, output offsets) is then computed inside the epilogue.  Left to itself the
+  // compiler computes these per-lane constants once, ahead of the persistent tile loop, finds no
+  // registers for them across the K loop and reloads them from scratch in the epilogue, each
+  // reload waiting for the stores issued before it.
+  int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  asm volatile("" : "+v"(lane), "+v"(wave));
   const int wr = wave / WC, wc = wave % WC;
   const int li = lane & 31, lh = lane >> 5;
   if constexpr (Epi::kRowRuns) {
@@ -109,6 +115,7 @@ __device__ __forceinline__ void gemm_tile_epilogue(const f32x16 (&acc)[BM / WR /
       return POW2 ? (chunk ^ ((row / RPLC) & (CPRW - 1))) : (chunk + row) % CPRW;
     };
     unsigned char* cst = stage + wave * (32 * ROWB);
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave), wr_u = wave_u / WC, wc_u = wave_u % WC;   // known to be uniform
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -123,13 +130,40 @@ __device__ __forceinline__ void gemm_tile_epilogue(const f32x16 (&acc)[BM / WR /
           for (int e = 0; e < 4; ++e) o[e] = (bf16_t)v[e];
           *(bf16x4*)(cst + li * ROWB + (swz(li, 4 * j + gq) << 4) + lh * 8) = o;
         }
+      constexpr int NIT = 32 * CPRW / 64;
+      if (bm0 + BM <= M && bn0 + BN <= N) {
+        // a whole tile (wave-uniform): all reads of the pass in flight together, no predicates,
+        // and for the row-major outputs a wave-uniform row pointer plus a 32-bit lane offset
+        constexpr int RB = NIT % 4 == 0 ? 4 : NIT % 3 == 0 ? 3 : NIT % 2 == 0 ? 2 : 1;   // reads in flight together
+        const int m0 = bm0 + wr_u * WTM + i * 32, nb = bn0 + wc_u * WTN;
 #pragma unroll
-      for (int it = 0; it < 32 * CPRW / 64; ++it) {
-        const int idx = it * 64 + lane;
-        const int row = idx / CPRW, chunk = idx % CPRW;
-        const bf16x8 o = *(const bf16x8*)(cst + row * ROWB + (swz(row, chunk) << 4));
-        const int m = bm0 + wr * WTM + i * 32 + row, n0 = bn0 + wc * WTN + chunk * 8;
-        if (m < M && n0 < N) __builtin_nontemporal_store(o, (bf16x8*)epi.run8(m, n0));
+        for (int it0 = 0; it0 < NIT; it0 += RB) {
+          bf16x8 o[RB];
+#pragma unroll
+          for (int r = 0; r < RB; ++r) {
+            const int idx = (it0 + r) * 64 + lane;
+            const int row = idx / CPRW, chunk = idx % CPRW;
+            o[r] = *(const bf16x8*)(cst + row * ROWB + (swz(row, chunk) << 4));
+          }
+#pragma unroll
+          for (int r = 0; r < RB; ++r) {
+            const int idx = (it0 + r) * 64 + lane;
+            const int row = idx / CPRW, chunk = idx % CPRW;
+            if constexpr (Epi::kLinearOut)
+              __builtin_nontemporal_store(o[r], (bf16x8*)(epi.row_ptr(m0, nb) + ((unsigned)row * (unsigned)epi.P.ldo + (unsigned)chunk * 8u)));
+            else
+              __builtin_nontemporal_store(o[r], (bf16x8*)epi.run8(m0 + row, nb + chunk * 8));
+          }
+        }
+      } else {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+          const int idx = it * 64 + lane;
+          const int row = idx / CPRW, chunk = idx % CPRW;
+          const bf16x8 o = *(const bf16x8*)(cst + row * ROWB + (swz(row, chunk) << 4));
+          const int m = bm0 + wr * WTM + i * 32 + row, n0 = bn0 + wc * WTN + chunk * 8;
+          if (m < M && n0 < N) __builtin_nontemporal_store(o, (bf16x8*)epi.run8(m, n0));
+        }
       }
     }
   } else {
@@ -178,6 +212,13 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds_any(const bf16_t* __
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave / WC, wc = wave % WC;
   const int li = lane & 31, lh = lane >> 5;
+  // an absent bias reads as zeros, an absent gate as ones (written once: no DMA touches them)
+  if constexpr (Epi::kRowRuns) {
+    if (tid < 256) {
+      if (!epi.P.bias) sbias[tid] = 0.0f;
+      if (Epi::kHasGate && !epi.P.gate) sgate[tid] = 1.0f;
+    }
+  }
 
   // ---- tiles of this workgroup: virtual ids blockIdx.x, + gridDim.x, ... below `padded`
   // (the grid may be one workgroup per slot of the chip: persistent).  gridDim.x is a
@@ -415,6 +456,13 @@ __global__ __launch_bounds__(WR * WC * 64) void k_gemm_dlds(const bf16_t* __rest
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave / WC, wc = wave % WC;
   const int li = lane & 31, lh = lane >> 5;
+  // an absent bias reads as zeros, an absent gate as ones (written once: no DMA touches them)
+  if constexpr (Epi::kRowRuns) {
+    if (tid < 256) {
+      if (!epi.P.bias) sbias[tid] = 0.0f;
+      if (Epi::kHasGate && !epi.P.gate) sgate[tid] = 1.0f;
+    }
+  }
 
   // ---- units of work (as in k_gemm_dlds_any; split ranges start at even K tiles)
   const int total = tiles_m * tiles_n;
