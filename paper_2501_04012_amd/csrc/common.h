@@ -182,6 +182,19 @@ struct Epilogue {
   }
   // Row-major outputs: address of (m, n) for wave-uniform m and n
   __device__ __forceinline__ T* row_ptr(int m, int n) const { return (T*)P.out + (size_t)m * P.ldo + n; }
+  // EPI_HEADS, the two halves of run8: the column's part of the address (tensor, head, offset in
+  // the head: fixed for a lane over a whole tile when its column is) and the row's part.
+  __device__ __forceinline__ T* head_col_ptr(int n0) const {
+    const unsigned w = col_D.div((unsigned)n0), cc = (unsigned)n0 - w * col_D.d;
+    const unsigned head = col_hd.div(cc), dd = cc - head * col_hd.d;
+    const int which = P.which0 + (int)w;
+    T* base = (T*)(which == 0 ? P.q : which == 1 ? P.k : P.v);
+    return base + (size_t)head * P.tokens * P.hd + dd;
+  }
+  __device__ __forceinline__ size_t head_row_off(int m) const {
+    const unsigned bb = rows_per_b.div((unsigned)m);
+    return ((size_t)m + (size_t)bb * (P.heads - 1) * P.tokens) * P.hd;
+  }
   // Address of outputs (m, n0 .. n0+7), n0 % 8 == 0: one 16-byte run in every row-run mode.
   __device__ __forceinline__ T* run8(int m, int n0) const {
     if constexpr (MODE == EPI_HEADS) {

@@ -136,6 +136,10 @@ __device__ __forceinline__ void gemm_tile_epilogue(const f32x16 (&acc)[BM / WR /
         // and for the row-major outputs a wave-uniform row pointer plus a 32-bit lane offset
         constexpr int RB = NIT % 4 == 0 ? 4 : NIT % 3 == 0 ? 3 : NIT % 2 == 0 ? 2 : 1;   // reads in flight together
         const int m0 = bm0 + wr_u * WTM + i * 32, nb = bn0 + wc_u * WTN;
+        // per-head outputs: with 64 % CPRW == 0 a lane keeps its column over all passes
+        constexpr bool kFixedCol = !Epi::kLinearOut && 64 % CPRW == 0;
+        bf16_t* colp = nullptr;
+        if constexpr (kFixedCol) colp = epi.head_col_ptr(nb + (lane % CPRW) * 8);
 #pragma unroll
         for (int it0 = 0; it0 < NIT; it0 += RB) {
           bf16x8 o[RB];
@@ -151,6 +155,8 @@ __device__ __forceinline__ void gemm_tile_epilogue(const f32x16 (&acc)[BM / WR /
             const int row = idx / CPRW, chunk = idx % CPRW;
             if constexpr (Epi::kLinearOut)
               __builtin_nontemporal_store(o[r], (bf16x8*)(epi.row_ptr(m0, nb) + ((unsigned)row * (unsigned)epi.P.ldo + (unsigned)chunk * 8u)));
+            else if constexpr (kFixedCol)
+              __builtin_nontemporal_store(o[r], (bf16x8*)(colp + epi.head_row_off(m0 + row)));
             else
               __builtin_nontemporal_store(o[r], (bf16x8*)epi.run8(m0 + row, nb + chunk * 8));
           }
