@@ -101,6 +101,34 @@ def test_linear_bf16_split_k_remainder(fc, M, N, K, epilogue):
     assert torch.equal(out2, ref)
 
 
+def test_linear_bf16_operand_beyond_32_bit_offsets(fc):
+    """An activation matrix of more than 4 GB: the tile kernel's buffer-addressed form covers
+    32-bit ranges only, so the dispatcher must hand this product to the general form.  The
+    operand is drawn on the device (it is 4.3 GB) with a seeded generator; the float64 product
+    is checked on sampled rows copied back to the host, the rest for finiteness."""
+    torch = _torch()
+    M, N, K = 65600 + 37, 256, 32768
+    assert M * K * 2 >= 2 ** 32
+    g = torch.Generator(device="cuda:0").manual_seed(4321)
+    A = torch.randn((M, K), device="cuda:0", generator=g, dtype=torch.float32).to(torch.bfloat16)
+    rng = np.random.default_rng(99)
+    W = BF(rng.standard_normal((K, N), dtype=np.float32) * np.float32(1 / math.sqrt(K)))
+    b = rng.standard_normal(N, dtype=np.float32)
+    out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+    fc.fc_op_linear(fc.FC_BF16, A, dev(W.T.copy(), True), dev(b), None, out, M, N, K, 0)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out.float()).all())
+    rows = np.unique(np.concatenate([np.arange(0, 4), np.arange(M - 4, M), rng.integers(0, M, 56),
+                                     [32767, 32768, 65535, 65536]]))      # around 2^31 and 2^32 bytes of row offset
+    idx = torch.from_numpy(rows).to("cuda:0")
+    a_rows = A.index_select(0, idx).float().cpu().numpy().astype(np.float64)
+    want = a_rows @ W.astype(np.float64) + b
+    got = out.index_select(0, idx).float().cpu().numpy()
+    record(rel_l2=rel_l2(got, want), max_abs=max_abs(got, want))
+    assert rel_l2(got, want) < 4e-3
+    assert (np.abs(got - want) <= 2.0 ** -8 * np.abs(want) + 2e-2).all()
+
+
 @pytest.mark.parametrize("M,N,K", [(1, 1, 1), (70, 65, 33), (256, 64, 64)])
 def test_linear_fp32(fc, M, N, K):
     torch = _torch()
