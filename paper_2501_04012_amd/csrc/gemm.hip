@@ -929,6 +929,17 @@ static hipError_t dispatch_mode(int bf16, const void* A, const void* Wt, int M, 
   const double waste = (double)ceil_div(N, 256) * 256.0 / N - 1.0;
   if (N % 192 == 0 && waste > 0.05 && (long long)ceil_div(M, 256) * (N / 192) >= 192)
     return run_dlds<256, 192, 64, 4, 2, 2, MODE>(A, Wt, M, N, K, ep, scratch, scratch_bytes, s);
+  // 384x192 (96x96 per wave) is no faster per tile than 256x256, but where its tile count fills
+  // whole rounds of 256 and that of 256x256 does not, it saves most of a round (the full-3D
+  // out-projection and fc2: 752 tiles = 2.94 rounds against 840 = 3.28; 2-5 % over the split
+  // last round)
+  if constexpr (MODE != EPI_UNPATCH) if (N % 192 == 0 && K >= 2048 && tiles256 >= 600) {
+    const long long t384 = (long long)ceil_div(M, 384) * (N / 192);
+    const double fill384 = (double)t384 / (double)((t384 + 255) / 256 * 256);
+    const double fill256 = (double)tiles256 / (double)((tiles256 + 255) / 256 * 256);
+    if (fill384 >= 0.95 && fill256 < 0.85 && waste <= 0.05)
+      return run_dlds<384, 192, 64, 4, 2, 2, MODE>(A, Wt, M, N, K, ep, scratch, scratch_bytes, s);
+  }
   if (tiles256 >= 600 && (waste <= 0.05 || K >= 2048)) return run_dlds<256, 256, 64, 4, 2, 2, MODE>(A, Wt, M, N, K, ep, scratch, scratch_bytes, s);
   return run_dlds<128, 128, 64, 2, 2, 2, MODE>(A, Wt, M, N, K, ep, scratch, scratch_bytes, s);
 }
