@@ -24,6 +24,22 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
 
+def ln_bytes_per_element(launches: int, esz: int) -> int:
+    """Bytes per residual-stream element that the LayerNorm launches of one step move: every
+    launch reads x (fp32) and writes its output (activation type); it also reads the branch
+    outputs not yet added to x, one after a launch that wrote x back (or the first), two
+    otherwise, and writes x back (fp32) when it has read two.  The last launch never writes x."""
+    total, pending = 0, 0
+    for i in range(launches):
+        total += 4 + esz + pending * esz
+        if pending == 2 and i < launches - 1:
+            total += 4
+        if pending == 2:
+            pending = 0
+        pending += 1
+    return total
+
+
 def measured_traffic(kernel):
     """(HBM bytes per launch of `kernel`, where the figure comes from): the bytes are replayed
     from the committed rocprofv3 counter summary, not counted in this run; (None, reason) when
@@ -483,8 +499,7 @@ def main():
     nmod = 9 if factorized else 6
     lat_elems = R * cfg.frames * cfg.height * cfg.width * cfg.channels
     per_step_bytes = {
-        # x (fp32) in, out (act) out; every launch but the first also folds a branch in: + y in, x out
-        "ln_modulate": elems * ((4 + esz) + (ln_launches - 1) * (4 + esz + esz + 4)),
+        "ln_modulate": elems * ln_bytes_per_element(ln_launches, esz),
         "patch_embed": forwards * cfg.video_tokens * cfg.hidden * 4,
         "timestep_modulation": (cfg.depth * nmod + 2) * cfg.hidden * cfg.hidden * esz
                                + (cfg.t_embed_dim + cfg.hidden) * cfg.hidden * esz,

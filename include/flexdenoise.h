@@ -311,6 +311,17 @@ int fc_op_layernorm_modulate(int32_t dtype, float* x, const void* y, const float
                              const float* scale, void* out, int32_t M, int32_t D, float eps,
                              void* hip_stream);
 
+/* The same with the residual additions as a step defers them (the pre-LN block of the DiT
+ * sections: x <- x + gate * branch(LayerNorm(x)), one addition per branch): up to two pending
+ * branch outputs y, y2 (act, [M,D]; y2 only together with y), each with an optional per-column
+ * gate (f32 [D], NULL = ones), are added in that order to the row in fp32,
+ *   v = (x + gate * y) + gate2 * y2,   out = LayerNorm(v) * (1 + scale) + shift,
+ * and v is written back to x only if write_x is non-zero; otherwise x is left as it is and the
+ * caller passes the same y again with the next branch's output. */
+int fc_op_layernorm_residual2(int32_t dtype, float* x, const void* y, const float* gate, const void* y2,
+                              const float* gate2, const float* shift, const float* scale, void* out,
+                              int32_t M, int32_t D, float eps, int32_t write_x, void* hip_stream);
+
 /* Patch embedding with positions: x[b, row_off + n, :] (f32, rows of D, rows_per_b rows per
  * batch row) = patch(latent[b % R], n) . Wp[p*p*C, D] + bp[D] + pos_sp[s, :] + pos_t[t, :],
  * n = t*S + s, S = (H/p)*(W/p), latent [R, T, H, W, C] f32, patch features in (dh, dw, c)

@@ -78,6 +78,8 @@ EXPORTS = {
                                 C.c_int32, C.c_void_p, C.c_void_p],
     "fc_op_layernorm_modulate": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                  C.c_int32, C.c_float, C.c_void_p],
+    "fc_op_layernorm_residual2": [C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                  C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_int32, C.c_void_p],
     "fc_op_patch_embed": [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                           C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
                           C.c_int32, C.c_void_p],
@@ -311,6 +313,12 @@ def fc_op_attention_bounded(q, k, v, out, G, nq, nk, d, key_norm_scratch, stream
 def fc_op_layernorm_modulate(dtype, x, y, shift, scale, out, M, D, eps, stream=None) -> None:
     _check(_lib.fc_op_layernorm_modulate(dtype, _ptr(x), _ptr(y), _ptr(shift), _ptr(scale), _ptr(out), M, D, eps,
                                          _stream(stream)), "fc_op_layernorm_modulate")
+
+
+def fc_op_layernorm_residual2(dtype, x, y, gate, y2, gate2, shift, scale, out, M, D, eps, write_x, stream=None) -> None:
+    _check(_lib.fc_op_layernorm_residual2(dtype, _ptr(x), _ptr(y), _ptr(gate), _ptr(y2), _ptr(gate2), _ptr(shift),
+                                          _ptr(scale), _ptr(out), M, D, eps, int(write_x), _stream(stream)),
+           "fc_op_layernorm_residual2")
 
 
 def fc_op_patch_embed(latent, R, B, Wp, bp, pos_sp, pos_t, x, T, H, W, Cc, p, D, rows_per_b, row_off, impl=0,

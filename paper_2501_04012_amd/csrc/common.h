@@ -272,10 +272,10 @@ hipError_t launch_gemv(int bf16, const float* in, int K, const void* Wt, const f
 hipError_t launch_patch_embed(const float* latent, int R, int B, const float* Wp, const float* bp,
                               const float* pos_sp, const float* pos_t, float* x, int T, int H, int W, int C,
                               int p, int D, int rows_per_b, int row_off, int impl, hipStream_t s);
-hipError_t launch_ln_modulate(int bf16, float* x, const void* y, const float* gate, const float* shift,
-                              const float* scale, void* out, int rows, int D, float eps, int in_rows_per_b,
-                              int out_rows_per_b, int in_row_off, int alt_rows, int alt_off, int write_x,
-                              hipStream_t s);
+hipError_t launch_ln_modulate(int bf16, float* x, const void* y, const float* gate, const void* y2,
+                              const float* gate2, const float* shift, const float* scale, void* out, int rows, int D,
+                              float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off, int alt_rows,
+                              int alt_off, int write_x, hipStream_t s);
 hipError_t launch_cfg_ddim(float* x, const float* eps_c, const float* eps_u, float* eps_out, size_t n,
                            float gscale, float c0, float c1, float c2, float c3, hipStream_t s);
 hipError_t launch_cfg_ddim_noise(float* x, const float* eps_c, const float* eps_u, float* eps_out, size_t per_request,

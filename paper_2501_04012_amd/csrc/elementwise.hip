@@ -381,18 +381,21 @@ hipError_t launch_patch_embed(const float* latent, int R, int B, const float* Wp
 // ---------------------------------------------------------------- residual add + LayerNorm + modulate
 // One wave per row, the row held in registers (NCH 16-byte chunks per lane, all loads
 // issued before the first use).  If `y` is given, the pending branch output of the
-// previous linear layer is folded in first: x <- x + gate * y (gate NULL = ones; written
-// back in fp32 unless write_x is 0, which the last LayerNorm of a step passes: x is not read
-// after it), then
+// previous linear layer is folded in first: x <- x + gate * y (gate NULL = ones), and after
+// it a second one, `y2` with `gate2`, if given.  The sum is written back in fp32 only if
+// write_x is set: a caller that keeps y pending and passes it again with the next branch's
+// output saves one write and one read of x for one more read of y (half the size), with the
+// same additions in the same order; the last LayerNorm of a step never writes x.  Then
 //   out = (x - mean) * rsqrt(var + eps) * (1 + scale) + shift
 // with mean and centred variance as wave reductions (two passes over registers).
 // Output row r reads input row (r / out_rows_per_b) * in_rows_per_b + in_row_off +
 // r % out_rows_per_b, which lets the output head skip text rows.  Rows whose position in
 // their sequence (in_row_off + r % out_rows_per_b) is below alt_rows read shift, scale and
 // gate alt_off floats further on: the text rows' own modulation set.
-template <typename T, int NCH>
+template <typename T, int NCH, bool TWO>
 __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, const T* __restrict__ y,
-                                                     const float* __restrict__ gate, const float* __restrict__ shift,
+                                                     const float* __restrict__ gate, const T* __restrict__ y2,
+                                                     const float* __restrict__ gate2, const float* __restrict__ shift,
                                                      const float* __restrict__ scale, T* __restrict__ out, int rows, int D,
                                                      float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off,
                                                      int alt_rows, int alt_off, int write_x) {
@@ -403,19 +406,21 @@ __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, cons
   const size_t in_r = (size_t)(r / out_rows_per_b) * in_rows_per_b + pos;
   if (pos < alt_rows) {                 // wave-uniform
     if (gate) gate += alt_off;
+    if (gate2) gate2 += alt_off;
     if (scale) { scale += alt_off; shift += alt_off; }
   }
   float* xr = x + in_r * D;
-  // every load of the row (x, the pending y, gate, scale, shift) is issued before the first
-  // use: the kernel lives on loads in flight, not on arithmetic
+  // every load of the row (x, the pending y and y2, scale, shift) is issued before the
+  // first use: the kernel lives on loads in flight, not on arithmetic
   // (for rows of up to 1280 elements; wider rows would need more registers than leave
   // enough waves per SIMD, and read y, gate, scale and shift chunk by chunk instead)
   constexpr bool BATCH = NCH <= 5;
   constexpr int NB = BATCH ? NCH : 1;
   typedef typename std::conditional<sizeof(T) == 2, bf16x4, f32x4>::type yvec;
-  f32x4 v[NCH], gv[NB], scv[NB], shv[NB];
-  yvec yv[NB];
+  f32x4 v[NCH], scv[NB], shv[NB];
+  yvec yv[NB], yv2[TWO ? NB : 1];
   const T* yr = y ? y + in_r * D : nullptr;
+  const T* yr2 = TWO ? y2 + in_r * D : nullptr;
 #pragma unroll
   for (int j = 0; j < NCH; ++j) {
     const int c = lane * 4 + j * 256;
@@ -428,12 +433,12 @@ __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, cons
         const int c = lane * 4 + j * 256;
         if (c < D) yv[j] = *(const yvec*)(yr + c);
       }
-      if (gate) {
+    }
+    if constexpr (TWO) {
 #pragma unroll
-        for (int j = 0; j < NCH; ++j) {
-          const int c = lane * 4 + j * 256;
-          if (c < D) gv[j] = *(const f32x4*)(gate + c);
-        }
+      for (int j = 0; j < NCH; ++j) {
+        const int c = lane * 4 + j * 256;
+        if (c < D) yv2[j] = *(const yvec*)(yr2 + c);
       }
     }
     if (scale) {
@@ -452,14 +457,20 @@ __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, cons
         const int jb = BATCH ? j : 0;
         if constexpr (!BATCH) {
           yv[0] = *(const yvec*)(yr + c);
-          if (gate) gv[0] = *(const f32x4*)(gate + c);
+          if constexpr (TWO) yv2[0] = *(const yvec*)(yr2 + c);
         }
         f32x4 yf;
 #pragma unroll
         for (int e = 0; e < 4; ++e) yf[e] = (float)yv[jb][e];
-        if (gate) yf = yf * gv[jb];
+        if (gate) yf = yf * *(const f32x4*)(gate + c);       // per-row gates: the rare case, read at use
         v[j] += yf;
-        if (write_x) *(f32x4*)(xr + c) = v[j];     // not after the last block: x is not read again
+        if constexpr (TWO) {                  // only ever given together with y
+#pragma unroll
+          for (int e = 0; e < 4; ++e) yf[e] = (float)yv2[jb][e];
+          if (gate2) yf = yf * *(const f32x4*)(gate2 + c);
+          v[j] += yf;
+        }
+        if (write_x) *(f32x4*)(xr + c) = v[j];
       }
     }
   }
@@ -500,13 +511,22 @@ __global__ __launch_bounds__(256) void k_ln_modulate(float* __restrict__ x, cons
 }
 
 template <typename T>
-static hipError_t run_ln(float* x, const void* y, const float* gate, const float* shift, const float* scale, void* out,
+static hipError_t run_ln(float* x, const void* y, const float* gate, const void* y2, const float* gate2,
+                         const float* shift, const float* scale, void* out,
                          int rows, int D, float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off, int alt_rows,
                          int alt_off, int write_x, hipStream_t s) {
   dim3 grid(ceil_div(rows, 4));
 #define FC_LN(N)                                                                                                   \
-  k_ln_modulate<T, N><<<grid, 256, 0, s>>>(x, (const T*)y, gate, shift, scale, (T*)out, rows, D, eps, in_rows_per_b, \
-                                           out_rows_per_b, in_row_off, alt_rows, alt_off, write_x)
+  do {                                                                                                              \
+    if (y2)                                                                                                         \
+      k_ln_modulate<T, N, true><<<grid, 256, 0, s>>>(x, (const T*)y, gate, (const T*)y2, gate2, shift, scale, (T*)out, \
+                                                     rows, D, eps, in_rows_per_b, out_rows_per_b, in_row_off,       \
+                                                     alt_rows, alt_off, write_x);                                   \
+    else                                                                                                            \
+      k_ln_modulate<T, N, false><<<grid, 256, 0, s>>>(x, (const T*)y, gate, nullptr, nullptr, shift, scale, (T*)out, \
+                                                      rows, D, eps, in_rows_per_b, out_rows_per_b, in_row_off,      \
+                                                      alt_rows, alt_off, write_x);                                  \
+  } while (0)
   if (D <= 256) FC_LN(1);
   else if (D <= 1280) FC_LN(5);
   else if (D <= 3072) FC_LN(12);
@@ -516,16 +536,17 @@ static hipError_t run_ln(float* x, const void* y, const float* gate, const float
   return hipGetLastError();
 }
 
-hipError_t launch_ln_modulate(int bf16, float* x, const void* y, const float* gate, const float* shift,
-                              const float* scale, void* out, int rows, int D, float eps, int in_rows_per_b,
-                              int out_rows_per_b, int in_row_off, int alt_rows, int alt_off, int write_x,
-                              hipStream_t s) {
+hipError_t launch_ln_modulate(int bf16, float* x, const void* y, const float* gate, const void* y2,
+                              const float* gate2, const float* shift, const float* scale, void* out, int rows, int D,
+                              float eps, int in_rows_per_b, int out_rows_per_b, int in_row_off, int alt_rows,
+                              int alt_off, int write_x, hipStream_t s) {
   if (rows == 0) return hipSuccess;
+  if (y2 && !y) return hipErrorInvalidValue;
   if (bf16)
-    return run_ln<bf16_t>(x, y, gate, shift, scale, out, rows, D, eps, in_rows_per_b, out_rows_per_b, in_row_off,
-                          alt_rows, alt_off, write_x, s);
-  return run_ln<float>(x, y, gate, shift, scale, out, rows, D, eps, in_rows_per_b, out_rows_per_b, in_row_off, alt_rows,
-                       alt_off, write_x, s);
+    return run_ln<bf16_t>(x, y, gate, y2, gate2, shift, scale, out, rows, D, eps, in_rows_per_b, out_rows_per_b,
+                          in_row_off, alt_rows, alt_off, write_x, s);
+  return run_ln<float>(x, y, gate, y2, gate2, shift, scale, out, rows, D, eps, in_rows_per_b, out_rows_per_b, in_row_off,
+                       alt_rows, alt_off, write_x, s);
 }
 
 // ---------------------------------------------------------------- guidance + DDIM update

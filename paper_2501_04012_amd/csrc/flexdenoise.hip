@@ -242,6 +242,7 @@ struct Workspace {
   void *xk, *xv;                           // cross-attention K / V per block (factorized)
   float* x;                                // residual stream fp32 [B, Ns, D]
   void *u, *q, *k, *v, *hid;               // activations
+  void* p[2];                              // gated branch outputs not yet added to x
   float* eps;                              // [B, T, H, W, C]
   float* knorm;                            // [B, heads, kKeyNormChunks] largest key norms (long-sequence attention)
   size_t bytes;
@@ -273,6 +274,8 @@ Workspace carve(const fc_model* m, int R, int use_cfg, unsigned char* base) {
   w.k = cv.take(rows * D * es);
   w.v = cv.take(rows * D * es);
   w.hid = cv.take(rows * c.mlp_dim * es);
+  w.p[0] = cv.take(rows * D * es);
+  w.p[1] = cv.take(rows * D * es);
   w.eps = (float*)cv.take((size_t)w.B * c.frames * c.height * c.width * c.channels * 4);
   w.knorm = (float*)cv.take((size_t)w.B * c.heads * kKeyNormChunks * 4);
   w.bytes = cv.off;
@@ -285,12 +288,16 @@ struct Ctx {
   Workspace w;
   int R, use_cfg;
   hipStream_t s;
-  // A branch's gated output sits in w.q, not yet added to the residual stream: the next
-  // LayerNorm launch folds it in (x <- x + y) while it has the row in registers.
-  mutable bool pending = false;
-  // Gate the fold applies to it (NULL: the projection's epilogue has applied it already).
+  // Gated branch outputs sit in w.p[0 .. npend), not yet added to the residual stream: the
+  // next LayerNorm launch adds them to the row it holds in registers.  With one pending it
+  // leaves x in memory as it is and keeps the branch pending; with two it writes the sum
+  // back.  x (fp32) is thus written and read every other LayerNorm, for one more read of a
+  // branch output of half its size; the additions and their order are those of adding each
+  // branch as it arrives.
+  mutable int npend = 0;
+  // Gate the fold applies to each (NULL: the projection's epilogue has applied it already).
   // Used when the text rows have their own modulation set: the gate then depends on the row.
-  mutable const float* pending_gate = nullptr;
+  mutable const float* pend_gate[2] = {nullptr, nullptr};
   int alt_rows() const { return m->cfg.text_adaln ? m->cfg.text_len : 0; }
   size_t act_bytes() const { return (size_t)w.B * m->Ns * m->cfg.hidden * m->esz; }   // one of u, q, k, v
   int alt_off() const { return 6 * m->cfg.hidden; }
@@ -368,23 +375,28 @@ int prepare(const Ctx& c, const float* cond, const float* null_cond) {
 int ln_mod(const Ctx& c, const float* shift, const float* scale) {
   const fc_model* m = c.m;
   ProfScope ps(c, PC_LN_MODULATE);
-  HIP_TRY(launch_ln_modulate(m->bf16, c.w.x, c.pending ? c.w.q : nullptr, c.pending ? c.pending_gate : nullptr, shift,
-                             scale, c.w.u, c.w.B * m->Ns, m->cfg.hidden, m->cfg.ln_eps, m->Ns, m->Ns, 0, c.alt_rows(),
-                             c.alt_off(), 1, c.s));
-  c.pending = false;
+  const int np = c.npend;
+  HIP_TRY(launch_ln_modulate(m->bf16, c.w.x, np > 0 ? c.w.p[0] : nullptr, np > 0 ? c.pend_gate[0] : nullptr,
+                             np > 1 ? c.w.p[1] : nullptr, np > 1 ? c.pend_gate[1] : nullptr, shift, scale, c.w.u,
+                             c.w.B * m->Ns, m->cfg.hidden, m->cfg.ln_eps, m->Ns, m->Ns, 0, c.alt_rows(), c.alt_off(),
+                             np == 2, c.s));
+  if (np == 2) c.npend = 0;
   return FC_OK;
 }
 
-// Branch output projection: y = gate * (A W + b) into w.q (q, k, v are dead by then).
+// Branch output projection: y = gate * (A W + b) into the next free pending buffer (the
+// LayerNorm that opened this branch has left at most one in use).
 int branch_out(const Ctx& c, int cat, const void* A, const Linear& L, const float* gate) {
+  if (c.npend > 1) return fail(FC_ERR_STATE, "no free buffer for a branch output");
   EpiParams ep;
   const bool by_row = c.m->cfg.text_adaln != 0;      // the fold picks the row's gate instead
-  ep.out = c.w.q; ep.ldo = c.m->cfg.hidden; ep.gate = by_row ? nullptr : gate;
+  ep.out = c.w.p[c.npend]; ep.ldo = c.m->cfg.hidden; ep.gate = by_row ? nullptr : gate;
   // k is dead by now (attention is over; the MLP never used it) and is neither operand nor output here
   int rc = linear(c, cat, EPI_GATE, A, L, c.w.B * c.m->Ns, ep, c.w.k, c.act_bytes());
-  c.pending = rc == FC_OK;
-  c.pending_gate = by_row ? gate : nullptr;
-  return rc;
+  if (rc != FC_OK) return rc;
+  c.pend_gate[c.npend] = by_row ? gate : nullptr;
+  ++c.npend;
+  return FC_OK;
 }
 
 // Self-attention branch: x += gate * proj(attn(qkv(u))).  mode 0 spatial, 1 temporal, 2 all tokens.
@@ -513,9 +525,11 @@ int run_step(const Ctx& c, float* latent, const fc_schedule* sched, int step, fl
   // head: LN + modulate on the video rows, Linear D -> p*p*C, scatter back to latent layout
   {
   ProfScope ps(c, PC_LN_MODULATE);
-  HIP_TRY(launch_ln_modulate(m->bf16, w.x, c.pending ? w.q : nullptr, c.pending ? c.pending_gate : nullptr, w.fmod,
-                             w.fmod + D, w.u, w.B * m->N, D, cf.ln_eps, m->Ns, m->N, text_rows, 0, 0, 0, c.s));
-  c.pending = false;
+  const int np = c.npend;
+  HIP_TRY(launch_ln_modulate(m->bf16, w.x, np > 0 ? w.p[0] : nullptr, np > 0 ? c.pend_gate[0] : nullptr,
+                             np > 1 ? w.p[1] : nullptr, np > 1 ? c.pend_gate[1] : nullptr, w.fmod, w.fmod + D, w.u,
+                             w.B * m->N, D, cf.ln_eps, m->Ns, m->N, text_rows, 0, 0, 0, c.s));
+  c.npend = 0;
   }
   EpiParams ep;
   ep.eps = w.eps; ep.T = cf.frames; ep.H = cf.height; ep.W = cf.width; ep.C = cf.channels; ep.p = cf.patch;
@@ -877,8 +891,21 @@ int fc_op_layernorm_modulate(int32_t dtype, float* x, const void* y, const float
   if (!x || !out) return fail(FC_ERR_NULL, "NULL argument");
   if ((shift == nullptr) != (scale == nullptr)) return fail(FC_ERR_NULL, "shift and scale go together");
   if (M < 0 || D < 4 || D % 4 || D > 4096) return fail(FC_ERR_RANGE, "D must be a multiple of 4 in 4..4096");
-  HIP_TRY(launch_ln_modulate(dtype == FC_BF16, x, y, nullptr, shift, scale, out, M, D, eps, M > 0 ? M : 1, M > 0 ? M : 1, 0, 0, 0, 1,
+  HIP_TRY(launch_ln_modulate(dtype == FC_BF16, x, y, nullptr, nullptr, nullptr, shift, scale, out, M, D, eps, M > 0 ? M : 1, M > 0 ? M : 1, 0, 0, 0, 1,
                              (hipStream_t)stream));
+  return FC_OK;
+}
+
+int fc_op_layernorm_residual2(int32_t dtype, float* x, const void* y, const float* gate, const void* y2,
+                              const float* gate2, const float* shift, const float* scale, void* out, int32_t M,
+                              int32_t D, float eps, int32_t write_x, void* stream) {
+  if (!x || !out) return fail(FC_ERR_NULL, "NULL argument");
+  if ((shift == nullptr) != (scale == nullptr)) return fail(FC_ERR_NULL, "shift and scale go together");
+  if (y2 && !y) return fail(FC_ERR_NULL, "y2 is given without y");
+  if ((gate && !y) || (gate2 && !y2)) return fail(FC_ERR_NULL, "a gate is given without its branch output");
+  if (M < 0 || D < 4 || D % 4 || D > 4096) return fail(FC_ERR_RANGE, "D must be a multiple of 4 in 4..4096");
+  HIP_TRY(launch_ln_modulate(dtype == FC_BF16, x, y, gate, y2, gate2, shift, scale, out, M, D, eps, M > 0 ? M : 1,
+                             M > 0 ? M : 1, 0, 0, 0, write_x != 0, (hipStream_t)stream));
   return FC_OK;
 }
 

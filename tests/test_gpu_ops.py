@@ -332,6 +332,50 @@ def test_layernorm_modulate(fc, M, D, bf, mod):
     assert np.array_equal(host(dx), x)                        # no pending branch: x untouched
 
 
+@pytest.mark.parametrize("M,D", [(37, 1152), (130, 3072), (9, 4096), (3, 260), (5, 4)])
+@pytest.mark.parametrize("bf", [False, True])
+@pytest.mark.parametrize("gated", [False, True])
+def test_layernorm_with_deferred_residual_additions(fc, M, D, bf, gated):
+    """The residual additions of a pre-LN block, two per write of x: the first call adds one
+    pending branch output and must leave x untouched, the second adds both and writes the sum.
+    Expected values: x + g1 y1 (+ g2 y2) in float64 on the values the kernel is given (branch
+    outputs rounded to the activation type first), then the oracle's LayerNorm and modulation."""
+    torch = _torch()
+    rng = np.random.default_rng(7 * M + D)
+    x = rng.standard_normal((M, D), dtype=np.float32) * 3 + 1
+    y1 = rng.standard_normal((M, D), dtype=np.float32)
+    y2 = rng.standard_normal((M, D), dtype=np.float32) * 2
+    if bf:
+        y1, y2 = BF(y1), BF(y2)
+    g1 = rng.standard_normal(D, dtype=np.float32) if gated else None
+    g2 = rng.standard_normal(D, dtype=np.float32) if gated else None
+    sh, sc = rng.standard_normal(D, dtype=np.float32), rng.standard_normal(D, dtype=np.float32)
+    code = fc.FC_BF16 if bf else fc.FC_F32
+    tdt = torch.bfloat16 if bf else torch.float32
+    f64 = lambda a: np.asarray(a, dtype=np.float64)
+    v1 = f64(x) + (f64(g1) if gated else 1.0) * f64(y1)
+    v2 = v1 + (f64(g2) if gated else 1.0) * f64(y2)
+    dx, dy1, dy2 = dev(x), dev(y1, bf), dev(y2, bf)
+    dg1, dg2 = (dev(g1), dev(g2)) if gated else (None, None)
+    out = torch.empty((M, D), dtype=tdt, device="cuda:0")
+    # one pending, not written back
+    fc.fc_op_layernorm_residual2(code, dx, dy1, dg1, None, None, dev(sh), dev(sc), out, M, D, 1e-6, 0)
+    torch.cuda.synchronize()
+    assert rel_l2(host(out), dit.modulate(dit.layernorm(v1, 1e-6), sh, sc)) < (4e-3 if bf else 2e-6)
+    assert np.array_equal(host(dx), x)
+    # both, written back
+    fc.fc_op_layernorm_residual2(code, dx, dy1, dg1, dy2, dg2, None, None, out, M, D, 1e-6, 1)
+    torch.cuda.synchronize()
+    assert rel_l2(host(out), dit.layernorm(v2, 1e-6)) < (4e-3 if bf else 2e-6)
+    assert np.abs(host(dx) - v2).max() <= 2e-6 * np.abs(v2).max() + 1e-6
+    # the same sum as adding each branch when it arrives (two writes of x): bit for bit
+    dx2 = dev(x)
+    fc.fc_op_layernorm_residual2(code, dx2, dy1, dg1, None, None, None, None, out, M, D, 1e-6, 1)
+    fc.fc_op_layernorm_residual2(code, dx2, dy2, dg2, None, None, None, None, out, M, D, 1e-6, 1)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(dx2), host(dx))
+
+
 @pytest.mark.parametrize("impl", [1, 2])
 @pytest.mark.parametrize("shape", [
     # T, H, W, C, D, R, B, row_off
