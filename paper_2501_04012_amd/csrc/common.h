@@ -268,7 +268,8 @@ hipError_t launch_act_to_f32_rows(int bf16, const void* in, float* out, int rows
 hipError_t launch_sinusoid(float t, int dim, float* out, hipStream_t s);
 hipError_t launch_gemv(int bf16, const float* in, int K, const void* Wt, const float* bias, float* out, int N,
                        int in_silu, int out_silu, int layers, size_t w_layer_stride, size_t b_layer_stride,
-                       size_t out_layer_stride, hipStream_t s);
+                       size_t out_layer_stride, hipStream_t s, const void* Wt2 = nullptr,
+                       const float* bias2 = nullptr, float* out2 = nullptr, int N2 = 0);
 hipError_t launch_patch_embed(const float* latent, int R, int B, const float* Wp, const float* bp,
                               const float* pos_sp, const float* pos_t, float* x, int T, int H, int W, int C,
                               int p, int D, int rows_per_b, int row_off, int impl, hipStream_t s);

@@ -94,34 +94,59 @@ hipError_t launch_sinusoid(float t, int dim, float* out, hipStream_t s) {
 // ---------------------------------------------------------------- GEMV
 // out[l][n] = f_out( sum_k f_in(in[k]) * Wt[l][n][k] + bias[l][n] ): a wave owns NOUT
 // consecutive outputs, lanes stride K with 16-byte loads, the weight loads of all NOUT
-// rows of a K slice are in flight together.  The input vector is shared by all layers l
-// (the adaLN layers of every block read the same SiLU(c)); a workgroup stages it in LDS
-// once, 16-byte chunk q at position q ^ ((q >> 4) & 1) so that the two chunks a lane reads
-// per step (2 lane, 2 lane + 1) fall into distinct banks across 16 lanes.
+// rows of a K slice are in flight together and run one slice ahead of the arithmetic; the
+// first slice is requested before the input vector is staged, so that staging (a dependent
+// load, SiLU, an LDS write and a barrier) costs no memory time.  The input vector is shared by
+// all layers l (the adaLN layers of every block read the same SiLU(c)); a workgroup stages it
+// in LDS once, 16-byte chunk q at position q ^ ((q >> 4) & 1) so that the two chunks a lane
+// reads per step (2 lane, 2 lane + 1) fall into distinct banks across 16 lanes.
+// A second product on the same input (Wt2, bias2, out2, N2: one layer) can ride in the same
+// launch: its workgroups follow the first product's in layer 0 of the grid.
 template <typename T, int NOUT>
 __global__ __launch_bounds__(256) void k_gemv(const float* __restrict__ in, int K, const T* __restrict__ Wt,
                                               const float* __restrict__ bias, float* __restrict__ out, int N, int in_silu,
                                               int out_silu, size_t w_layer_stride, size_t b_layer_stride,
-                                              size_t out_layer_stride) {
+                                              size_t out_layer_stride, const T* __restrict__ Wt2,
+                                              const float* __restrict__ bias2, float* __restrict__ out2, int N2) {
   extern __shared__ __attribute__((aligned(16))) float s_in[];
   constexpr int V = 16 / sizeof(T);          // weights per 16-byte load
+  typedef typename std::conditional<sizeof(T) == 2, bf16x8, f32x4>::type wvec;
   const bool vec = K % V == 0;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nb1 = (N + 4 * NOUT - 1) / (4 * NOUT);            // workgroups of the first product
+  int bx = blockIdx.x;
+  const T* w; const float* bs; float* dst; int n_out;
+  if (bx < nb1) {
+    w = Wt + blockIdx.y * w_layer_stride; bs = bias + blockIdx.y * b_layer_stride;
+    dst = out + blockIdx.y * out_layer_stride; n_out = N;
+  } else {
+    if (blockIdx.y != 0) return;
+    bx -= nb1; w = Wt2; bs = bias2; dst = out2; n_out = N2;
+  }
+  const int n0 = (bx * 4 + wave) * NOUT;
+  const bool active = n0 < n_out;                              // wave-uniform
+  w += (size_t)n0 * K;
+  auto fetch = [&](int k, wvec (&r)[NOUT]) {
+#pragma unroll
+    for (int o = 0; o < NOUT; ++o)
+      if (n0 + o < n_out && k < K) r[o] = *(const wvec*)(w + (size_t)o * K + k);
+  };
+  wvec cur[NOUT], nxt[NOUT];
+  if (active && vec) fetch(lane * V, cur);
+
   for (int k = threadIdx.x; k < K; k += blockDim.x) {
     float v = in[k];
     const int q = k >> 2;
     s_in[vec ? ((q ^ ((q >> 4) & 1)) << 2) + (k & 3) : k] = in_silu ? silu_f(v) : v;
   }
   __syncthreads();
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int n0 = (blockIdx.x * (blockDim.x >> 6) + wave) * NOUT;
-  const int l = blockIdx.y;
-  if (n0 >= N) return;
-  const T* w = Wt + l * w_layer_stride + (size_t)n0 * K;
+  if (!active) return;
   float acc[NOUT];
 #pragma unroll
   for (int o = 0; o < NOUT; ++o) acc[o] = 0.0f;
   if (vec) {
     for (int k = lane * V; k < K; k += 64 * V) {
+      fetch(k + 64 * V, nxt);
       float x[V];
 #pragma unroll
       for (int c = 0; c < V / 4; ++c) {
@@ -132,31 +157,26 @@ __global__ __launch_bounds__(256) void k_gemv(const float* __restrict__ in, int 
       }
 #pragma unroll
       for (int o = 0; o < NOUT; ++o) {
-        if (n0 + o < N) {                      // wave-uniform
-          if constexpr (sizeof(T) == 2) {
-            const bf16x8 wv = *(const bf16x8*)(w + (size_t)o * K + k);
+        if (n0 + o < n_out) {                  // wave-uniform
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[o] += x[e] * (float)wv[e];
-          } else {
-            const f32x4 wv = *(const f32x4*)(w + (size_t)o * K + k);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[o] += x[e] * wv[e];
-          }
+          for (int e = 0; e < V; ++e) acc[o] += x[e] * (float)cur[o][e];
         }
       }
+#pragma unroll
+      for (int o = 0; o < NOUT; ++o) cur[o] = nxt[o];
     }
   } else {
     for (int k = lane; k < K; k += 64)
 #pragma unroll
       for (int o = 0; o < NOUT; ++o)
-        if (n0 + o < N) acc[o] += s_in[k] * to_f32(w[(size_t)o * K + k]);
+        if (n0 + o < n_out) acc[o] += s_in[k] * to_f32(w[(size_t)o * K + k]);
   }
 #pragma unroll
   for (int o = 0; o < NOUT; ++o) {
     const float a = wave_sum(acc[o]);
-    if (lane == 0 && n0 + o < N) {
-      float v = a + bias[l * b_layer_stride + n0 + o];
-      out[l * out_layer_stride + n0 + o] = out_silu ? silu_f(v) : v;
+    if (lane == 0 && n0 + o < n_out) {
+      float v = a + bs[n0 + o];
+      dst[n0 + o] = out_silu ? silu_f(v) : v;
     }
   }
 }
@@ -164,27 +184,32 @@ __global__ __launch_bounds__(256) void k_gemv(const float* __restrict__ in, int 
 template <typename T>
 static hipError_t run_gemv(const float* in, int K, const void* Wt, const float* bias, float* out, int N, int in_silu,
                            int out_silu, int layers, size_t w_layer_stride, size_t b_layer_stride,
-                           size_t out_layer_stride, hipStream_t s) {
+                           size_t out_layer_stride, const void* Wt2, const float* bias2, float* out2, int N2,
+                           hipStream_t s) {
   const size_t sh = ((size_t)K + 3) / 4 * 4 * sizeof(float) + 16;      // the chunk swap may touch one chunk past K
-  // 8 outputs per wave where that still leaves several workgroups per CU; else one each
-  if ((long long)ceil_div(N, 32) * layers >= 512)
-    k_gemv<T, 8><<<dim3(ceil_div(N, 32), layers), 256, sh, s>>>(in, K, (const T*)Wt, bias, out, N, in_silu, out_silu,
-                                                               w_layer_stride, b_layer_stride, out_layer_stride);
-  else
-    k_gemv<T, 1><<<dim3(ceil_div(N, 4), layers), 256, sh, s>>>(in, K, (const T*)Wt, bias, out, N, in_silu, out_silu,
-                                                              w_layer_stride, b_layer_stride, out_layer_stride);
+  // 8 outputs per wave where that still leaves several workgroups per CU; else 4, else one each
+  const long long outs = (long long)N * layers + N2;
+#define FC_GEMV(NOUT)                                                                                               \
+  k_gemv<T, NOUT><<<dim3(ceil_div(N, 4 * NOUT) + ceil_div(N2, 4 * NOUT), layers), 256, sh, s>>>(                    \
+      in, K, (const T*)Wt, bias, out, N, in_silu, out_silu, w_layer_stride, b_layer_stride, out_layer_stride,       \
+      (const T*)Wt2, bias2, out2, N2)
+  if (outs >= 8 * 4 * 2048) FC_GEMV(8);
+  else if (outs >= 4 * 4 * 1024) FC_GEMV(4);
+  else FC_GEMV(1);
+#undef FC_GEMV
   return hipGetLastError();
 }
 
 hipError_t launch_gemv(int bf16, const float* in, int K, const void* Wt, const float* bias, float* out, int N,
                        int in_silu, int out_silu, int layers, size_t w_layer_stride, size_t b_layer_stride,
-                       size_t out_layer_stride, hipStream_t s) {
+                       size_t out_layer_stride, hipStream_t s, const void* Wt2, const float* bias2, float* out2,
+                       int N2) {
   if (N == 0 || layers == 0) return hipSuccess;
   if (bf16)
     return run_gemv<bf16_t>(in, K, Wt, bias, out, N, in_silu, out_silu, layers, w_layer_stride, b_layer_stride,
-                            out_layer_stride, s);
+                            out_layer_stride, Wt2, bias2, out2, N2, s);
   return run_gemv<float>(in, K, Wt, bias, out, N, in_silu, out_silu, layers, w_layer_stride, b_layer_stride,
-                         out_layer_stride, s);
+                         out_layer_stride, Wt2, bias2, out2, N2, s);
 }
 
 // ---------------------------------------------------------------- patch embedding

@@ -488,8 +488,12 @@ int run_step(const Ctx& c, float* latent, const fc_schedule* sched, int step, fl
   HIP_TRY(launch_sinusoid((float)t, cf.t_embed_dim, w.e, c.s));
   HIP_TRY(launch_gemv(m->bf16, w.e, cf.t_embed_dim, m->t1.wt, m->t1.b, w.h1, D, 0, 1, 1, 0, 0, 0, c.s));
   HIP_TRY(launch_gemv(m->bf16, w.h1, D, m->t2.wt, m->t2.b, w.c, D, 0, 0, 1, 0, 0, 0, c.s));
-  HIP_TRY(launch_gemv(m->bf16, w.c, D, m->mod_w, m->mod_b, w.mod, nm, 1, 0, cf.depth, (size_t)nm * D, nm, nm, c.s));
-  HIP_TRY(launch_gemv(m->bf16, w.c, D, m->fmod.wt, m->fmod.b, w.fmod, 2 * D, 1, 0, 1, 0, 0, 0, c.s));
+  // the blocks' modulation vectors and the final layer's, both from SiLU(c): one launch
+  if (cf.depth > 0)
+    HIP_TRY(launch_gemv(m->bf16, w.c, D, m->mod_w, m->mod_b, w.mod, nm, 1, 0, cf.depth, (size_t)nm * D, nm, nm, c.s,
+                        m->fmod.wt, m->fmod.b, w.fmod, 2 * D));
+  else
+    HIP_TRY(launch_gemv(m->bf16, w.c, D, m->fmod.wt, m->fmod.b, w.fmod, 2 * D, 1, 0, 1, 0, 0, 0, c.s));
   }
 
   // tokens
